@@ -1,0 +1,378 @@
+// The C ABI of include/audiokv.h: host-side validation, workspace carving and
+// kernel enqueues. Nothing here allocates device memory or synchronises.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+using namespace audiokv;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t hip_fail(hipError_t e, const char* what) {
+    return fail(AUDIOKV_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Batch {
+    int n_items = 0;
+    int max_L = 0, min_L = 0;
+    long long total_tokens = 0;
+    bool uniform = true;
+};
+
+// window_min: smallest legal window for the calling entry point (score needs >= 1, select accepts 0)
+int32_t check_params(const audiokv_params* p, int window_min) {
+    if (!p) return fail(AUDIOKV_E_INVALID_ARG, "params is NULL");
+    if (p->size != sizeof(audiokv_params))
+        return fail(AUDIOKV_E_INVALID_ARG, "params.size = %u, this library expects %zu", p->size, sizeof(audiokv_params));
+    if (p->n_kv_heads < 1 || p->n_q_heads < 1 || p->n_q_heads % p->n_kv_heads != 0)
+        return fail(AUDIOKV_E_INVALID_ARG, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)",
+                    p->n_q_heads, p->n_kv_heads);
+    if (p->head_dim != 64 && p->head_dim != 128 && p->head_dim != 256)
+        return fail(AUDIOKV_E_UNSUPPORTED, "head_dim %d: only 64, 128 and 256 are built", p->head_dim);
+    if (p->window < window_min) return fail(AUDIOKV_E_INVALID_ARG, "window %d < %d", p->window, window_min);
+    if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0 || p->pool_kernel > 1025)
+        return fail(AUDIOKV_E_INVALID_ARG, "pool_kernel %d must be odd, in [1, 1025]", p->pool_kernel);
+    if (p->pool_mode != AUDIOKV_POOL_AVG && p->pool_mode != AUDIOKV_POOL_MAX)
+        return fail(AUDIOKV_E_INVALID_ARG, "pool_mode %d", p->pool_mode);
+    if (p->kv_layout != AUDIOKV_LAYOUT_HEAD_MAJOR && p->kv_layout != AUDIOKV_LAYOUT_TOKEN_MAJOR)
+        return fail(AUDIOKV_E_INVALID_ARG, "kv_layout %d", p->kv_layout);
+    if (p->causal != 0 && p->causal != 1) return fail(AUDIOKV_E_INVALID_ARG, "causal %d", p->causal);
+    if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale))
+        return fail(AUDIOKV_E_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 selects 1/sqrt(d))");
+    if (!(p->floor_frac >= 0.f && p->floor_frac <= 1.f))
+        return fail(AUDIOKV_E_INVALID_ARG, "floor_frac must lie in [0, 1]");
+    return AUDIOKV_OK;
+}
+
+int32_t check_batch(const audiokv_params* p, int32_t n_items, const int32_t* seqlens_host, Batch* b) {
+    if (n_items < 1) return fail(AUDIOKV_E_INVALID_ARG, "n_items %d < 1", n_items);
+    if (!seqlens_host) return fail(AUDIOKV_E_INVALID_ARG, "seqlens_host is NULL");
+    b->n_items = n_items;
+    b->max_L = 0;
+    b->min_L = INT32_MAX;
+    b->total_tokens = 0;
+    for (int i = 0; i < n_items; ++i) {
+        const int L = seqlens_host[i];
+        if (L < 1 || L < p->window)
+            return fail(AUDIOKV_E_INVALID_ARG, "item %d: length %d must be >= max(1, window = %d)", i, L, p->window);
+        b->max_L = L > b->max_L ? L : b->max_L;
+        b->min_L = L < b->min_L ? L : b->min_L;
+        b->total_tokens += L;
+    }
+    b->uniform = b->max_L == b->min_L;
+    if (b->total_tokens * p->n_kv_heads > (long long)INT32_MAX)
+        return fail(AUDIOKV_E_UNSUPPORTED, "batch too large: %lld tokens x %d heads exceeds 2^31 scores",
+                    b->total_tokens, p->n_kv_heads);
+    if ((long long)n_items * p->n_kv_heads > (1 << 20))
+        return fail(AUDIOKV_E_UNSUPPORTED, "too many heads in one call");
+    return AUDIOKV_OK;
+}
+
+Geom make_geom(const audiokv_params* p, int n_items) {
+    Geom g;
+    g.n_items = n_items;
+    g.H_q = p->n_q_heads;
+    g.H_kv = p->n_kv_heads;
+    g.G = p->n_q_heads / p->n_kv_heads;
+    g.D = p->head_dim;
+    g.W = p->window;
+    g.pool_kernel = p->pool_kernel;
+    g.pool_mode = p->pool_mode;
+    g.causal = p->causal;
+    g.layout = p->kv_layout;
+    const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)p->head_dim);
+    g.c_log2 = scale * 1.44269504088896340736f;
+    return g;
+}
+
+struct Workspace {
+    size_t stats_off = 0, raw_off = 0, smooth_off = 0, total = 0;
+};
+
+Workspace plan_workspace(const audiokv_params* p, const Batch& b) {
+    Workspace w;
+    const int n_heads = b.n_items * p->n_kv_heads;
+    const int rows = (p->n_q_heads / p->n_kv_heads) * (p->window > 0 ? p->window : 1);
+    const int rows_pad = score_padded_rows(rows, p->head_dim);
+    const int nsplit = score_num_splits(n_heads, b.max_L, rows, p->head_dim);
+    size_t off = 0;
+    w.stats_off = off;
+    off += align_up((size_t)n_heads * nsplit * (rows_pad > 0 ? rows_pad : 1) * 2 * sizeof(float), 256);
+    w.raw_off = off;
+    off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
+    w.smooth_off = off;
+    off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
+    w.total = off;
+    return w;
+}
+
+int32_t check_ratio(const audiokv_params* p, const Batch& b, const int32_t* seqlens_host, double ratio) {
+    if (!(ratio > 0.0 && ratio <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "ratio %g must lie in (0, 1]", ratio);
+    for (int i = 0; i < b.n_items; ++i) {
+        const int nk = audiokv_n_keep(ratio, seqlens_host[i]);
+        if (nk < p->window || nk > seqlens_host[i])
+            return fail(AUDIOKV_E_INVALID_ARG,
+                        "item %d: n_keep = round(%g * %d) = %d must lie in [window = %d, L]", i, ratio,
+                        seqlens_host[i], nk, p->window);
+    }
+    return AUDIOKV_OK;
+}
+
+int32_t check_smooth_args(double cutoff_frac, double alpha) {
+    if (!(cutoff_frac >= 0.0 && cutoff_frac <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "cutoff_frac %g must lie in [0, 1]", cutoff_frac);
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "alpha %g must lie in [0, 1]", alpha);
+    return AUDIOKV_OK;
+}
+
+int32_t check_smooth_lengths(const Batch& b, const int32_t* seqlens_host, double alpha) {
+    if (alpha == 0.0) return AUDIOKV_OK;
+    for (int i = 0; i < b.n_items; ++i)
+        if (!smooth_supported(seqlens_host[i]))
+            return fail(AUDIOKV_E_UNSUPPORTED, "item %d: spectral smoothing of length %d is not built "
+                        "(power-of-two lengths from 4 to 32768)", i, seqlens_host[i]);
+    return AUDIOKV_OK;
+}
+
+int32_t check_score_shape(const audiokv_params* p) {
+    const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
+    if (score_padded_rows(rows, p->head_dim) == 0)
+        return fail(AUDIOKV_E_UNSUPPORTED, "group * window = %d rows at head_dim %d exceeds what the score kernels hold "
+                    "in registers (512 rows at d <= 128, 256 rows at d = 256)", rows, p->head_dim);
+    return AUDIOKV_OK;
+}
+
+#define AUDIOKV_TRY(expr)                  \
+    do {                                   \
+        const int32_t rc__ = (expr);       \
+        if (rc__ != AUDIOKV_OK) return rc__; \
+    } while (0)
+#define AUDIOKV_HIP(expr, what)                      \
+    do {                                             \
+        const hipError_t e__ = (expr);               \
+        if (e__ != hipSuccess) return hip_fail(e__, what); \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int32_t audiokv_version(void) { return 100; }   // 0.1.0
+
+const char* audiokv_last_error(void) { return g_err; }
+
+int32_t audiokv_n_keep(double ratio, int32_t L) {
+    volatile double prod = ratio * (double)L;    // volatile: no fused multiply-add on the host either
+    return (int32_t)std::floor(prod + 0.5);
+}
+
+int32_t audiokv_total_kept(const audiokv_params* params, int32_t n_items, const int32_t* seqlens_host,
+                           double ratio, int64_t* out_rows)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!out_rows) return fail(AUDIOKV_E_INVALID_ARG, "out_rows is NULL");
+    AUDIOKV_TRY(check_ratio(params, b, seqlens_host, ratio));
+    int64_t tot = 0;
+    for (int i = 0; i < n_items; ++i) tot += (int64_t)audiokv_n_keep(ratio, seqlens_host[i]) * params->n_kv_heads;
+    *out_rows = tot;
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_workspace_bytes(const audiokv_params* params, int32_t n_items, const int32_t* seqlens_host,
+                                size_t* out_bytes)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!out_bytes) return fail(AUDIOKV_E_INVALID_ARG, "out_bytes is NULL");
+    *out_bytes = plan_workspace(params, b).total;
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_score(const audiokv_params* params, const void* q_win, const void* k,
+                      const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                      float* scores, void* workspace, size_t workspace_bytes, void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 1));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!q_win || !k || !cu_seqlens_dev || !scores || !workspace)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_score: NULL pointer argument");
+    if (!aligned16(q_win) || !aligned16(k)) return fail(AUDIOKV_E_INVALID_ARG, "q_win and k must be 16-byte aligned");
+    AUDIOKV_TRY(check_score_shape(params));
+    const Workspace w = plan_workspace(params, b);
+    if (workspace_bytes < w.total)
+        return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+    const Geom g = make_geom(params, n_items);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    float* stats = reinterpret_cast<float*>(ws + w.stats_off);
+    float* raw = params->pool_kernel == 1 ? scores : reinterpret_cast<float*>(ws + w.raw_off);
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s), "score kernels");
+    if (params->pool_kernel != 1)
+        AUDIOKV_HIP(launch_pool(g, raw, cu_seqlens_dev, b.max_L, scores, s), "pool kernel");
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_allocate(const audiokv_params* params, const float* weights_dev, int32_t n_segments,
+                         int32_t heads_per_segment, int32_t weight_group, const int32_t* cu_seqlens_dev,
+                         const int32_t* seqlens_host, double ratio, int32_t* budgets_dev,
+                         int32_t* cu_budgets_dev, void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    if (n_segments < 1 || heads_per_segment < 1 || weight_group < 1)
+        return fail(AUDIOKV_E_INVALID_ARG, "n_segments, heads_per_segment and weight_group must be >= 1");
+    if (heads_per_segment > 1536)
+        return fail(AUDIOKV_E_UNSUPPORTED, "heads_per_segment %d > 1536", heads_per_segment);
+    if (!weights_dev || !cu_seqlens_dev || !seqlens_host || !budgets_dev || !cu_budgets_dev)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_allocate: NULL pointer argument");
+    if (!(ratio > 0.0 && ratio <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "ratio %g must lie in (0, 1]", ratio);
+    long long total = 0;
+    for (int s2 = 0; s2 < n_segments; ++s2) {
+        const int L = seqlens_host[s2];
+        if (L < 1) return fail(AUDIOKV_E_INVALID_ARG, "segment %d: length %d", s2, L);
+        const int nk = audiokv_n_keep(ratio, L);
+        if (nk < params->window || nk > L)
+            return fail(AUDIOKV_E_INVALID_ARG, "segment %d: n_keep = %d must lie in [window = %d, L = %d]", s2, nk,
+                        params->window, L);
+        total += (long long)nk * heads_per_segment;
+    }
+    if (total > (long long)INT32_MAX) return fail(AUDIOKV_E_UNSUPPORTED, "sum of budgets exceeds 2^31");
+    const Geom g = make_geom(params, n_segments);
+    AUDIOKV_HIP(launch_allocate(g, weights_dev, n_segments, heads_per_segment, weight_group, cu_seqlens_dev, ratio,
+                                (double)params->floor_frac, budgets_dev, cu_budgets_dev,
+                                static_cast<hipStream_t>(stream)),
+                "allocate kernel");
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, const int32_t* cu_seqlens_dev,
+                       const int32_t* seqlens_host, int32_t n_items, double cutoff_frac, double alpha,
+                       float* scores_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    AUDIOKV_TRY(check_params(params, 0));
+    audiokv_params p2 = *params;
+    p2.window = 0;                                // lengths are not tied to the window here
+    Batch b;
+    AUDIOKV_TRY(check_batch(&p2, n_items, seqlens_host, &b));
+    if (!scores_in || !scores_out || !cu_seqlens_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_smooth: NULL pointer argument");
+    AUDIOKV_TRY(check_smooth_args(cutoff_frac, alpha));
+    AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
+    const Geom g = make_geom(params, n_items);
+    AUDIOKV_HIP(launch_smooth(g, scores_in, false, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha,
+                              scores_out, static_cast<hipStream_t>(stream)),
+                "smooth kernel");
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_select(const audiokv_params* params, const float* scores, const int32_t* budgets_dev,
+                       const int32_t* cu_budgets_dev, const int32_t* cu_seqlens_dev, const int32_t* seqlens_host,
+                       int32_t n_items, int32_t* indices_dev, void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    AUDIOKV_TRY(check_params(params, 0));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!scores || !budgets_dev || !cu_budgets_dev || !cu_seqlens_dev || !indices_dev)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_select: NULL pointer argument");
+    if (!select_supported(b.max_L))
+        return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d exceeds 32768", b.max_L);
+    const Geom g = make_geom(params, n_items);
+    AUDIOKV_HIP(launch_select(g, scores, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev,
+                              static_cast<hipStream_t>(stream)),
+                "select kernel");
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_compact(const audiokv_params* params, const void* k, const void* v, const int32_t* indices_dev,
+                        const int32_t* cu_budgets_dev, const int32_t* cu_seqlens_dev, const int32_t* seqlens_host,
+                        int32_t n_items, int64_t total_rows, void* k_out, void* v_out, void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!k || !v || !indices_dev || !cu_budgets_dev || !cu_seqlens_dev || !k_out || !v_out)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_compact: NULL pointer argument");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(AUDIOKV_E_INVALID_ARG, "k, v, k_out and v_out must be 16-byte aligned");
+    if (total_rows < 0 || total_rows > b.total_tokens * params->n_kv_heads)
+        return fail(AUDIOKV_E_INVALID_ARG, "total_rows %lld outside [0, tokens x heads]", (long long)total_rows);
+    const Geom g = make_geom(params, n_items);
+    AUDIOKV_HIP(launch_compact(g, k, v, indices_dev, cu_budgets_dev, cu_seqlens_dev, total_rows, k_out, v_out,
+                               static_cast<hipStream_t>(stream)),
+                "compact kernel");
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const void* k, const void* v,
+                      const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
+                      const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
+                      void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev, int32_t* cu_budgets_dev,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 1));
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    if (!q_win || !k || !v || !weights_dev || !cu_seqlens_dev || !k_out || !v_out || !indices_dev || !budgets_dev ||
+        !cu_budgets_dev || !workspace)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_evict: NULL pointer argument");
+    if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(AUDIOKV_E_INVALID_ARG, "q_win, k, v, k_out and v_out must be 16-byte aligned");
+    if (alloc_scope != AUDIOKV_SCOPE_ITEM && alloc_scope != AUDIOKV_SCOPE_GLOBAL)
+        return fail(AUDIOKV_E_INVALID_ARG, "alloc_scope %d", alloc_scope);
+    if (alloc_scope == AUDIOKV_SCOPE_GLOBAL && !b.uniform)
+        return fail(AUDIOKV_E_INVALID_ARG, "a global budget pool needs equal lengths (got %d..%d)", b.min_L, b.max_L);
+    AUDIOKV_TRY(check_ratio(params, b, seqlens_host, ratio));
+    AUDIOKV_TRY(check_smooth_args(cutoff_frac, alpha));
+    AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
+    AUDIOKV_TRY(check_score_shape(params));
+    if (!select_supported(b.max_L)) return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d exceeds 32768", b.max_L);
+    const int n_heads = n_items * params->n_kv_heads;
+    if (alloc_scope == AUDIOKV_SCOPE_GLOBAL && n_heads > 1536)
+        return fail(AUDIOKV_E_UNSUPPORTED, "global pool of %d heads > 1536", n_heads);
+    const Workspace w = plan_workspace(params, b);
+    if (workspace_bytes < w.total)
+        return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+
+    const Geom g = make_geom(params, n_items);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    float* stats = reinterpret_cast<float*>(ws + w.stats_off);
+    float* raw = reinterpret_cast<float*>(ws + w.raw_off);
+    float* smoothed = reinterpret_cast<float*>(ws + w.smooth_off);
+    int64_t total_rows = 0;
+    for (int i = 0; i < n_items; ++i) total_rows += (int64_t)audiokv_n_keep(ratio, seqlens_host[i]) * params->n_kv_heads;
+
+    const int n_seg = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? 1 : n_items;
+    const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
+    AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
+                                budgets_dev, cu_budgets_dev, s), "allocate kernel");
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s), "score kernels");
+    AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
+                              alpha, smoothed, s), "smooth kernel");
+    AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
+                "select kernel");
+    AUDIOKV_HIP(launch_compact(g, k, v, indices_dev, cu_budgets_dev, cu_seqlens_dev, total_rows, k_out, v_out, s),
+                "compact kernel");
+    return AUDIOKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Shared declarations of the gfx950 kernels behind the AudioKV C ABI.
+// Device code only needs hip_runtime; nothing here depends on torch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "audiokv.h"
+
+namespace audiokv {
+
+// Geometry handed to kernels by value.
+struct Geom {
+    int n_items;
+    int H_q;
+    int H_kv;
+    int G;          // H_q / H_kv
+    int D;          // head_dim
+    int W;          // window
+    int pool_kernel;
+    int pool_mode;
+    int causal;
+    int layout;     // AUDIOKV_LAYOUT_*
+    float c_log2;   // softmax scale * log2(e): logits are handled in base-2 units
+};
+
+// Where head (item, h), token j starts inside the packed K/V buffers (in elements).
+__device__ __forceinline__ int64_t kv_row_offset(const Geom& g, int64_t item_tok0, int L, int h, int j) {
+    const int64_t base = item_tok0 * g.H_kv * g.D;
+    if (g.layout == AUDIOKV_LAYOUT_HEAD_MAJOR)
+        return base + ((int64_t)h * L + j) * g.D;
+    return base + ((int64_t)j * g.H_kv + h) * g.D;
+}
+
+// ---- launchers (defined in the .hip files, called from api.hip) ------------
+
+// Number of key-range splits per head used by the score kernels; a pure
+// function of the batch so that the workspace query and the launch agree.
+int score_num_splits(int n_heads_total, int max_L, int rows, int D);
+// Padded row count (multiple of the MFMA row tiling) for G*W window rows; 0 if unsupported.
+int score_padded_rows(int rows, int D);
+
+hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
+                        int max_L, float* stats_ws, float* raw_out, hipStream_t s);
+hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
+                       float* pooled, hipStream_t s);
+
+hipError_t launch_allocate(const Geom& g, const float* weights, int n_segments, int heads_per_segment,
+                           int weight_group, const int32_t* cu_seqlens, double ratio, double floor_frac,
+                           int32_t* budgets, int32_t* cu_budgets, hipStream_t s);
+
+// pool_on_load: input holds un-pooled scores and the pooling of Geom is applied while loading.
+bool smooth_supported(int L);
+hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
+                         const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
+                         float* out, hipStream_t s);
+
+bool select_supported(int L);
+hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budgets, const int32_t* cu_budgets,
+                         const int32_t* cu_seqlens, int max_L, int32_t* indices, hipStream_t s);
+
+hipError_t launch_compact(const Geom& g, const void* k, const void* v, const int32_t* indices,
+                          const int32_t* cu_budgets, const int32_t* cu_seqlens, int64_t total_rows,
+                          void* k_out, void* v_out, hipStream_t s);
+
+}  // namespace audiokv
