@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused AudioKV eviction path (audiokv_evict) on one MI355X.
+
+A "step" is one pass of the whole hot path (allocate, score, smooth, select,
+compact) over one batch of synthetic audio-shaped input: all layers of one
+configuration in one call. Inputs are resident in HBM before the timed region.
+Prints one JSON line:
+  value     = layer-tokens evicted per second: sum_items (L_i - n_keep_i) / step time
+  roofline  = the dominant kernel's algorithmic rate against its bound, with the
+              kernel duration measured by HIP events on the launch stream
+  cpu_baseline = the float64 oracle timed on this host on one layer of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import concurrent.futures as cf
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+# plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one fp32 op per lane per clock
+# (packed-fp32 forms are compiled out), i.e. half of the 157.3 TFLOP/s FMA figure counted as ops
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: 28 layers x L=32768, W=64)")
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--cutoff", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(cfg, lens, ratio):
+    """Bytes the method must move per step (one read of K for scoring, gather read + packed write of
+    kept K/V rows, one write + one read of the score vector and of the indices)."""
+    H, d = cfg.n_kv_heads, cfg.head_dim
+    from paper_2604_06694_amd import n_keep
+    per = {"score_read_k": 0, "compact": 0, "scores_rw": 0, "indices_rw": 0}
+    for L in lens:
+        nk = n_keep(ratio, L)
+        per["score_read_k"] += L * H * d * 2
+        per["compact"] += 4 * nk * H * d * 2
+        per["scores_rw"] += 2 * 4 * L * H
+        per["indices_rw"] += 2 * 4 * nk * H
+    per["total"] = sum(per.values())
+    return per
+
+
+def cpu_baseline(cfg, item0, w, L, ratio, cutoff, alpha):
+    """The oracle as it stands on one layer (all KV heads) of the workload."""
+    import numpy as np
+    from oracle import audiokv_oracle as O
+    from workloads import bf16_bits_to_f64
+    t0 = time.perf_counter()
+    b, _ = O.allocate(w[:cfg.n_kv_heads].astype(np.float64), L, ratio, window=cfg.window,
+                      floor_frac=float(np.float32(cfg.floor_frac)))
+    _, _, idx = O.evict_item(bf16_bits_to_f64(item0["q_win"]), bf16_bits_to_f64(item0["k"]), b, window=cfg.window,
+                             pool_kernel=cfg.pool_kernel, cutoff_frac=cutoff, alpha=alpha)
+    O.compact(item0["k"], item0["v"], idx)
+    dt = time.perf_counter() - t0
+    nk = O.n_keep_of(ratio, L)
+    return {"value": (L - nk) / dt, "unit": "layer-tokens evicted/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"1 of {cfg.n_items} layers of the same workload (all {cfg.n_kv_heads} KV heads, L={L}); "
+                      "float64 numpy, BLAS threads as configured by the host"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2604_06694_amd as A
+    from workloads import gen_item, gen_lengths, gen_weights, get_config
+
+    over = {}
+    if args.ratio is not None:
+        over["ratio"] = args.ratio
+    if args.cutoff is not None:
+        over["cutoff"] = args.cutoff
+    cfg = get_config(args.config, **over)
+    lens = [int(x) for x in gen_lengths(cfg)]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
+        items = list(ex.map(lambda i: gen_item(cfg, i, seqlen=lens[i]), range(cfg.n_items)))
+
+    def to_dev(key):
+        flat = np.concatenate([it[key].reshape(-1) for it in items])
+        return torch.from_numpy(flat.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    q, k, v = to_dev("q_win"), to_dev("k"), to_dev("v")
+    w_host = gen_weights(cfg)
+    w = torch.from_numpy(w_host).to(dev)
+    item0 = items[0]
+    del items
+
+    p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window, pool_kernel=cfg.pool_kernel,
+                 floor_frac=cfg.floor_frac)
+    scope = A.SCOPE_GLOBAL if cfg.alloc_scope == "global" else A.SCOPE_ITEM
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    ws = torch.empty(A.workspace_bytes(p, lens), dtype=torch.uint8, device=dev)
+    outs: dict = {}
+
+    def step():
+        A.evict(p, q, k, v, w, lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=scope, cu_seqlens=cu,
+                workspace=ws, outputs=outs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # per-kernel durations: the same steps again with HIP events recorded between the kernels on the launch stream
+    A.profile_enable(True)
+    acc = {n: 0.0 for n in A.PROFILE_STAGES}
+    n_prof = max(3, min(args.steps, 10))
+    for _ in range(n_prof):
+        step()
+        for n, ms in A.profile_read().items():
+            acc[n] += ms
+    A.profile_enable(False)
+    stage_ms = {n: acc[n] / n_prof for n in acc}
+
+    tokens = sum(lens)
+    kept = sum(A.n_keep(cfg.ratio, L) for L in lens)
+    evicted = tokens - kept
+    ab = algorithmic_bytes(cfg, lens, cfg.ratio)
+    score_flops = sum(2.0 * cfg.n_q_heads * cfg.window * L * cfg.head_dim for L in lens)
+    score_exps = sum(float(cfg.n_q_heads * cfg.window * L) for L in lens)
+
+    dominant = max(stage_ms, key=stage_ms.get)
+    dom_s = stage_ms[dominant] * 1e-3
+    if dominant in ("score_sweep1", "score_sweep2"):
+        # each sweep performs the whole contraction once
+        roof = {"bound": "mfma", "achieved": score_flops / dom_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None,
+                "hbm_GBs_of_this_kernel": ab["score_read_k"] / dom_s / 1e9}
+    else:
+        key = {"compact": "compact", "pool_smooth": "scores_rw", "select": "indices_rw", "allocate": "indices_rw"}[dominant]
+        roof = {"bound": "hbm", "achieved": ab[key] / dom_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    res = {
+        "metric": "prefill KV tokens evicted/sec per layer (1 GPU) + achieved HBM GB/s fraction",
+        "value": evicted / dt,
+        "unit": "layer-tokens evicted/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_items": cfg.n_items, "n_q_heads": cfg.n_q_heads,
+                   "n_kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim, "window": cfg.window,
+                   "seqlen": lens[0] if len(set(lens)) == 1 else lens, "ratio": cfg.ratio, "cutoff": cfg.cutoff,
+                   "alpha": cfg.alpha, "pool_kernel": cfg.pool_kernel, "alloc_scope": cfg.alloc_scope},
+        "tokens_processed_per_s": tokens / dt,
+        "whole_path": {"algorithmic_bytes": ab["total"], "GBs": ab["total"] / dt / 1e9,
+                       "hbm_frac": ab["total"] / dt / 1e9 / HBM_PEAK_GBS, "us_per_layer": dt * 1e6 / cfg.n_items},
+        "stage_ms": stage_ms,
+        "score": {"TFLOPs_both_sweeps": 2 * score_flops / ((stage_ms["score_sweep1"] + stage_ms["score_sweep2"]) * 1e-3) / 1e12,
+                  "exp_per_s_both_sweeps": 2 * score_exps / ((stage_ms["score_sweep1"] + stage_ms["score_sweep2"]) * 1e-3)},
+        "compact_GBs": ab["compact"] / (stage_ms["compact"] * 1e-3) / 1e9,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, item0, w_host, lens[0], cfg.ratio, cfg.cutoff, cfg.alpha)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -199,6 +199,18 @@ int32_t audiokv_evict(const audiokv_params* params,
                       int32_t* budgets_dev, int32_t* cu_budgets_dev,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid, not part of the method (used by the benchmark to time the
+ * kernels of audiokv_evict where they run). While enabled, audiokv_evict records
+ * HIP events on the caller's stream between its kernels; audiokv_profile_read
+ * waits for the most recent such call to finish and writes the elapsed
+ * milliseconds of each interval to ms_out[AUDIOKV_PROFILE_STAGES] (host):
+ * 0 allocate, 1 score sweep 1 (row statistics), 2 score sweep 2 (column sums),
+ * 3 pooling + spectral smoothing, 4 select, 5 compact. Process-wide state (the
+ * events are created by the first enable and kept); not thread-safe. */
+#define AUDIOKV_PROFILE_STAGES 6
+int32_t audiokv_profile_enable(int32_t enable);
+int32_t audiokv_profile_read(float* ms_out);
+
 #ifdef __cplusplus
 }
 #endif

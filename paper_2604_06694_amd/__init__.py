@@ -1,23 +1,26 @@
 """MI355X (gfx950) implementation of AudioKV's prefill-time KV-cache eviction path.
 
 The work is done by hand-written HIP kernels behind the C ABI declared in
-include/audiokv.h (libaudiokv.so, built by paper_2604_06694_amd.build). This
-package is only the ctypes binding: argument marshalling, with torch used for
-device memory and streams. There is no CPU fallback: importing `binding`
-without the built library raises.
+include/audiokv.h (libaudiokv.so, built by `python -m paper_2604_06694_amd.build`).
+This package is only the ctypes binding: argument marshalling, with torch used
+for device memory and streams. There is no CPU fallback: the first use of any
+binding name without the built library raises ImportError.
+
+The binding is loaded on first attribute access so that the build module can be
+run before the library exists.
 """
-from .binding import (  # noqa: F401
-    AudioKVError,
-    Params,
-    allocate,
-    compact,
-    evict,
-    lib_path,
-    n_keep,
-    score,
-    select,
-    smooth,
-    total_kept,
-    version,
-    workspace_bytes,
+import importlib
+
+_BINDING_NAMES = (
+    "AudioKVError", "Params", "allocate", "compact", "evict", "lib_path", "n_keep", "profile_enable",
+    "profile_read", "score", "select", "smooth", "total_kept", "version", "workspace_bytes",
+    "POOL_AVG", "POOL_MAX", "LAYOUT_HEAD_MAJOR", "LAYOUT_TOKEN_MAJOR", "SCOPE_ITEM", "SCOPE_GLOBAL",
+    "PROFILE_STAGES",
 )
+
+
+def __getattr__(name):
+    if name == "binding" or name in _BINDING_NAMES:
+        b = importlib.import_module(".binding", __name__)
+        return b if name == "binding" else getattr(b, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -84,6 +84,10 @@ def _load() -> C.CDLL:
     lib.audiokv_compact.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.audiokv_evict.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
                                   vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.audiokv_profile_enable.argtypes = [i32]
+    lib.audiokv_profile_enable.restype = i32
+    lib.audiokv_profile_read.argtypes = [C.POINTER(C.c_float)]
+    lib.audiokv_profile_read.restype = i32
     for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "select", "compact", "evict"):
         getattr(lib, "audiokv_" + name).restype = i32
     return lib
@@ -251,3 +255,17 @@ def evict(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weig
     o["total_rows"] = rows
     o["workspace"] = ws
     return o
+
+
+PROFILE_STAGES = ("allocate", "score_sweep1", "score_sweep2", "pool_smooth", "select", "compact")
+
+
+def profile_enable(on: bool) -> None:
+    _check(_lib.audiokv_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """Milliseconds of each kernel of the most recent evict() issued while profiling was enabled."""
+    buf = (C.c_float * len(PROFILE_STAGES))()
+    _check(_lib.audiokv_profile_read(buf))
+    return {n: float(buf[i]) for i, n in enumerate(PROFILE_STAGES)}

@@ -157,6 +157,14 @@ int32_t check_score_shape(const audiokv_params* p) {
     return AUDIOKV_OK;
 }
 
+// stage timing for the benchmark: events 0..6 bracket the six kernels of audiokv_evict
+struct Profile {
+    bool enabled = false;
+    bool created = false;
+    bool recorded = false;
+    hipEvent_t ev[AUDIOKV_PROFILE_STAGES + 2] = {};    // last slot: between the two score sweeps
+} g_prof;
+
 #define AUDIOKV_TRY(expr)                  \
     do {                                   \
         const int32_t rc__ = (expr);       \
@@ -363,15 +371,52 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
 
     const int n_seg = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? 1 : n_items;
     const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
+    const bool prof = g_prof.enabled && g_prof.created;
+#define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
+    AUDIOKV_MARK(0);
     AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
                                 budgets_dev, cu_budgets_dev, s), "allocate kernel");
-    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s), "score kernels");
+    AUDIOKV_MARK(1);
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
+                             prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr), "score kernels");
+    AUDIOKV_MARK(2);
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, s), "smooth kernel");
+    AUDIOKV_MARK(3);
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
+    AUDIOKV_MARK(4);
     AUDIOKV_HIP(launch_compact(g, k, v, indices_dev, cu_budgets_dev, cu_seqlens_dev, total_rows, k_out, v_out, s),
                 "compact kernel");
+    AUDIOKV_MARK(5);
+#undef AUDIOKV_MARK
+    if (prof) g_prof.recorded = true;
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_profile_enable(int32_t enable)
+{
+    if (enable && !g_prof.created) {
+        for (auto& e : g_prof.ev) AUDIOKV_HIP(hipEventCreate(&e), "hipEventCreate");
+        g_prof.created = true;
+    }
+    g_prof.enabled = enable != 0;
+    g_prof.recorded = false;
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_profile_read(float* ms_out)
+{
+    if (!ms_out) return fail(AUDIOKV_E_INVALID_ARG, "ms_out is NULL");
+    if (!g_prof.created || !g_prof.recorded)
+        return fail(AUDIOKV_E_INVALID_ARG, "no profiled audiokv_evict call to read");
+    AUDIOKV_HIP(hipEventSynchronize(g_prof.ev[5]), "hipEventSynchronize");
+    hipEvent_t mid = g_prof.ev[AUDIOKV_PROFILE_STAGES + 1];
+    // intervals: [0,1] allocate, [1,mid] sweep 1, [mid,2] sweep 2, [2,3] smooth, [3,4] select, [4,5] compact
+    hipEvent_t a[AUDIOKV_PROFILE_STAGES] = {g_prof.ev[0], g_prof.ev[1], mid, g_prof.ev[2], g_prof.ev[3], g_prof.ev[4]};
+    hipEvent_t b[AUDIOKV_PROFILE_STAGES] = {g_prof.ev[1], mid, g_prof.ev[2], g_prof.ev[3], g_prof.ev[4], g_prof.ev[5]};
+    for (int i = 0; i < AUDIOKV_PROFILE_STAGES; ++i)
+        AUDIOKV_HIP(hipEventElapsedTime(&ms_out[i], a[i], b[i]), "hipEventElapsedTime");
     return AUDIOKV_OK;
 }
 

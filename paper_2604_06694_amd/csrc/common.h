@@ -40,8 +40,10 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D);
 // Padded row count (multiple of the MFMA row tiling) for G*W window rows; 0 if unsupported.
 int score_padded_rows(int rows, int D);
 
+// between_sweeps: optional event recorded on `s` after the first sweep (timing aid), or nullptr.
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
-                        int max_L, float* stats_ws, float* raw_out, hipStream_t s);
+                        int max_L, float* stats_ws, float* raw_out, hipStream_t s,
+                        hipEvent_t between_sweeps = nullptr);
 hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
                        float* pooled, hipStream_t s);
 

@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(
 
 template <int D, int NB, int WR>
 hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seq,
-                              int nsplit, float* stats, float* raw, hipStream_t s)
+                              int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between)
 {
     using T = Tile<D, NB, WR>;
     const int n_heads = g.n_items * g.H_kv;
@@ -328,6 +328,10 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
     }
     hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(kThreads), T::LDS_BYTES, s, g,
                        (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, raw);
+    if (between) {
+        const hipError_t e = hipEventRecord(between, s);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(kThreads), T::LDS_BYTES, s, g,
                        (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, raw);
     return hipGetLastError();
@@ -337,10 +341,10 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
 
 // one translation unit per head_dim keeps the build parallel
 hipError_t launch_score_d64(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-                            const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
 hipError_t launch_score_d128(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-                             const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
 hipError_t launch_score_d256(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-                             const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
 
 }  // namespace audiokv

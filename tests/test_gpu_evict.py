@@ -1,0 +1,187 @@
+"""End-to-end parity of the fused audiokv_evict against the float64 oracle on
+the synthetic workloads, through the C ABI.
+
+What is compared (per sampled head; budgets for every head):
+  * budgets: bit-exact with the oracle's allocation;
+  * kept index sets: agreement >= 99.9 % on average, and every index on which
+    the two differ must sit at the budget threshold: its oracle score within
+    2e-3 * max|s_hat| of the oracle's b-th largest score;
+  * compacted K/V: byte-exact gather of the GPU's own indices (and therefore of
+    the oracle's wherever the index sets agree);
+  * the fused call equals the five per-stage calls composed, bit for bit.
+"""
+import concurrent.futures as cf
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import audiokv_oracle as O
+from workloads import bf16_bits_to_f64, gen_item, gen_lengths, gen_weights, get_config
+
+from gpu_util import SCORE_RTOL, bf16_bits, bf16_tensor, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2604_06694_amd as A
+    return A
+
+
+_BATCH_CACHE = {}
+
+
+def make_batch(cfg, lens=None):
+    """Tensors depend only on the geometry and seeds, not on ratio / cutoff: reuse them across sweeps."""
+    lens = [int(x) for x in (lens if lens is not None else gen_lengths(cfg))]
+    key = (cfg.index, cfg.n_items, tuple(lens), cfg.window, cfg.n_spikes)
+    if key in _BATCH_CACHE:
+        return _BATCH_CACHE[key]
+    _BATCH_CACHE.clear()                      # keep at most one batch (the long one is ~2 GB)
+    _BATCH_CACHE[key] = _make_batch(cfg, lens)
+    return _BATCH_CACHE[key]
+
+
+def _make_batch(cfg, lens):
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
+        items = list(ex.map(lambda i: gen_item(cfg, i, seqlen=lens[i]), range(cfg.n_items)))
+    q = bf16_tensor(np.concatenate([it["q_win"].reshape(-1) for it in items]))
+    k = bf16_tensor(np.concatenate([it["k"].reshape(-1) for it in items]))
+    v = bf16_tensor(np.concatenate([it["v"].reshape(-1) for it in items]))
+    w = gen_weights(cfg)
+    return items, lens, q, k, v, w
+
+
+def oracle_budgets(cfg, w, lens):
+    S = w.astype(np.float64)
+    beta = float(np.float32(cfg.floor_frac))
+    if cfg.alloc_scope == "global":
+        b, _ = O.allocate(S, lens[0], cfg.ratio, window=cfg.window, floor_frac=beta)
+        return b
+    out = []
+    for i in range(cfg.n_items):
+        b, _ = O.allocate(S[i * cfg.n_kv_heads:(i + 1) * cfg.n_kv_heads], lens[i], cfg.ratio,
+                          window=cfg.window, floor_frac=beta)
+        out.append(b)
+    return np.concatenate(out)
+
+
+def run_and_check(A, cfg, sample_heads, lens=None):
+    items, lens, q, k, v, w = make_batch(cfg, lens)
+    p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window, pool_kernel=cfg.pool_kernel,
+                 floor_frac=cfg.floor_frac)
+    scope = 1 if cfg.alloc_scope == "global" else 0
+    out = A.evict(p, q, k, v, torch.from_numpy(w).cuda(), lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=scope)
+    torch.cuda.synchronize()
+    budgets = out["budgets"].cpu().numpy()
+    cu_b = out["cu_budgets"].cpu().numpy()
+    idx = out["indices"].cpu().numpy()
+    ko, vo = bf16_bits(out["k_out"]), bf16_bits(out["v_out"])
+    rows = out["total_rows"]
+
+    ref_b = oracle_budgets(cfg, w, lens)
+    assert np.array_equal(budgets, ref_b)
+    assert int(cu_b[-1]) == rows == sum(O.n_keep_of(cfg.ratio, L) for L in lens) * cfg.n_kv_heads
+
+    # every head: valid selection, byte-exact gather of the GPU's own indices
+    for g in range(len(budgets)):
+        it, h = items[g // cfg.n_kv_heads], g % cfg.n_kv_heads
+        L = it["seqlen"]
+        mine = idx[cu_b[g]:cu_b[g + 1]]
+        assert len(mine) == budgets[g] and np.all(np.diff(mine) > 0) and mine[0] >= 0 and mine[-1] == L - 1
+        assert np.array_equal(mine[-cfg.window:], np.arange(L - cfg.window, L))
+        assert np.array_equal(ko[cu_b[g]:cu_b[g + 1]], it["k"][h][mine])
+        assert np.array_equal(vo[cu_b[g]:cu_b[g + 1]], it["v"][h][mine])
+
+    # sampled heads: against the oracle's scores and selection
+    agree = []
+    for g in sample_heads:
+        it, h = items[g // cfg.n_kv_heads], g % cfg.n_kv_heads
+        L = it["seqlen"]
+        G = cfg.group
+        qf = bf16_bits_to_f64(it["q_win"][h * G:(h + 1) * G])
+        kf = bf16_bits_to_f64(it["k"][h:h + 1])
+        s = O.score(qf, kf, pool_kernel=cfg.pool_kernel)[0]
+        s_hat = O.smooth(s, cfg.cutoff, cfg.alpha)
+        ref = O.select(s_hat, int(ref_b[g]), cfg.window)
+        mine = idx[cu_b[g]:cu_b[g + 1]]
+        common = np.intersect1d(mine, ref)
+        agree.append(len(common) / len(ref))
+        diff = np.setxor1d(mine, ref)
+        if len(diff):
+            want = int(ref_b[g]) - cfg.window
+            thr = np.sort(s_hat[:L - cfg.window])[::-1][want - 1]
+            tol = SCORE_RTOL * np.abs(s_hat).max()
+            assert np.all(np.abs(s_hat[diff] - thr) <= tol), (g, np.abs(s_hat[diff] - thr).max(), tol)
+    assert np.mean(agree) >= 0.999, agree
+    return out, (items, lens, q, k, v, w, p, scope)
+
+
+def test_config1_full_and_fused_equals_composed(A):
+    cfg = get_config(1)
+    out, (items, lens, q, k, v, w, p, scope) = run_and_check(A, cfg, sample_heads=range(4))
+    # the five calls composed
+    s = A.score(p, q, k, lens)
+    b, cu = A.allocate(p, torch.from_numpy(w).cuda(), 1, cfg.n_kv_heads, lens, cfg.ratio)
+    sh = A.smooth(p, s, lens, cfg.cutoff, cfg.alpha)
+    idx = A.select(p, sh, b, cu, lens, out["total_rows"])
+    ko, vo = A.compact(p, k, v, idx, cu, lens, out["total_rows"])
+    torch.cuda.synchronize()
+    assert torch.equal(b, out["budgets"]) and torch.equal(cu, out["cu_budgets"])
+    assert torch.equal(idx, out["indices"][:out["total_rows"]])
+    assert torch.equal(ko.view(torch.int16), out["k_out"][:out["total_rows"]].view(torch.int16))
+    assert torch.equal(vo.view(torch.int16), out["v_out"][:out["total_rows"]].view(torch.int16))
+    # determinism: a second fused run is bit-identical
+    out2 = A.evict(p, q, k, v, torch.from_numpy(w).cuda(), lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=scope)
+    torch.cuda.synchronize()
+    assert torch.equal(out2["indices"], out["indices"])
+    assert torch.equal(out2["k_out"].view(torch.int16), out["k_out"].view(torch.int16))
+
+
+def test_config2_qwen25_omni_stack(A):
+    cfg = get_config(2)                      # 28 layers x L = 8192, global budget pool
+    run_and_check(A, cfg, sample_heads=[0, 1, 2, 3, 57, 110, 111])
+
+
+@pytest.mark.parametrize("ratio,cutoff", [(0.4, 0.125), (0.2, 0.25), (0.2, 0.0625)])
+def test_config3_long_audio_full_size(A, ratio, cutoff):
+    # the benchmark's launch configuration: all 28 layers of L = 32768 in one call
+    cfg = get_config(3, ratio=ratio, cutoff=cutoff)
+    run_and_check(A, cfg, sample_heads=[0, 3, 58, 111] if ratio == 0.4 else [5, 110])
+
+
+def test_config4_concentrated_weights(A):
+    cfg = get_config(4)                      # 48 layers x L = 16384; Dirichlet(0.2): the cap fires
+    out, _ = run_and_check(A, cfg, sample_heads=[0, 1, 95, 191])
+    b = out["budgets"].cpu().numpy()
+    assert b.max() == cfg.seqlen             # at least one head keeps everything
+
+
+def test_small_odd_shapes(A):
+    # ragged tail tiles, tiny L, window = L - small
+    for L, W, ratio in [(64, 8, 0.5), (128, 32, 0.4), (512, 64, 0.3), (1024, 32, 0.9)]:
+        cfg = get_config(1, seqlen=L, window=W, ratio=ratio, n_items=2, n_spikes=min(16, L - W))
+        run_and_check(A, cfg, sample_heads=range(8))
+
+
+def test_error_paths_return_codes_without_enqueueing(A):
+    cfg = get_config(1, seqlen=256)
+    items, lens, q, k, v, w = make_batch(cfg)
+    p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window)
+    wt = torch.from_numpy(w).cuda()
+    with pytest.raises(A.AudioKVError) as e:
+        A.evict(p, q, k, v, wt, lens, 0.01, 0.125, 1.0)          # n_keep < window
+    assert e.value.code == -1
+    with pytest.raises(A.AudioKVError) as e:
+        A.evict(p, q, k, v, wt, lens, 0.4, 1.5, 1.0)             # cutoff out of range
+    assert e.value.code == -1
+    with pytest.raises(A.AudioKVError) as e:
+        A.evict(p, q, k, v, wt, lens, 0.4, 0.125, 1.0, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -3
+    bad = A.Params(cfg.n_q_heads, cfg.n_kv_heads, 96, cfg.window)
+    with pytest.raises(A.AudioKVError) as e:
+        A.score(bad, q, k, lens)
+    assert e.value.code == -2
+    torch.cuda.synchronize()

@@ -37,10 +37,12 @@ from scipy.signal import lfilter
 
 def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round finite float64 values to bf16 (nearest even); returns uint16 bit patterns."""
-    f32 = np.ascontiguousarray(x, dtype=np.float32)
-    u = f32.view(np.uint32).astype(np.uint64)
-    u = u + 0x7FFF + ((u >> 16) & 1)
-    return ((u >> 16) & 0xFFFF).astype(np.uint16)
+    u = np.array(x, dtype=np.float32).view(np.uint32)      # private copy, modified in place
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u += lsb
+    u += np.uint32(0x7FFF)                                  # finite inputs: cannot wrap
+    u >>= np.uint32(16)
+    return u.astype(np.uint16)
 
 
 def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
