@@ -1,0 +1,93 @@
+"""The C-ABI library: it loads without a GPU, exports every symbol the header declares,
+and its host-side logic (sizes, rounding, validation) behaves as documented. No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2604_06694_amd as A
+    if not os.path.exists(os.path.join(ROOT, "paper_2604_06694_amd", "libaudiokv.so")):
+        from paper_2604_06694_amd import build
+        build.build()
+    return A
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "audiokv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(audiokv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(A):
+    names = declared_functions()
+    assert {"audiokv_score", "audiokv_allocate", "audiokv_smooth", "audiokv_select", "audiokv_compact",
+            "audiokv_evict"} <= set(names)
+    lib = C.CDLL(A.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_n_keep_matches_oracle_rounding(A):
+    from oracle import audiokv_oracle as O
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        L = int(rng.integers(1, 70000))
+        r = float(rng.uniform(0.01, 1.0))
+        assert A.n_keep(r, L) == O.n_keep_of(r, L)
+    for r, L in [(0.4, 2048), (0.2, 32768), (0.4, 32768), (0.3, 5003), (0.5, 5), (0.25, 10)]:
+        assert A.n_keep(r, L) == O.n_keep_of(r, L)
+    assert A.n_keep(0.4, 2048) == 819 and A.n_keep(0.4, 32768) == 13107 and A.n_keep(0.2, 32768) == 6554
+
+
+def test_total_kept_and_workspace(A):
+    p = A.Params(28, 4, 128, 64)
+    assert A.total_kept(p, [32768] * 28, 0.4) == 13107 * 4 * 28
+    assert A.total_kept(A.Params(8, 2, 256, 32), [2048, 5000], 0.3) == (614 + 1500) * 2
+    small = A.workspace_bytes(p, [4096])
+    big = A.workspace_bytes(p, [32768] * 28)
+    assert 0 < small < big
+    assert big >= 2 * 28 * 4 * 32768 * 4          # raw + smoothed scores
+
+
+def test_validation_errors_are_codes_not_crashes(A):
+    good = A.Params(28, 4, 128, 32)
+    cases = [
+        (A.Params(28, 5, 128, 32), -1),           # H_q not a multiple of H_kv
+        (A.Params(28, 4, 96, 32), -2),            # head_dim not built
+        (A.Params(28, 4, 128, 32, pool_kernel=4), -1),
+        (A.Params(28, 4, 128, 32, floor_frac=1.5), -1),
+        (A.Params(28, 4, 128, 32, kv_layout=7), -1),
+    ]
+    for p, code in cases:
+        with pytest.raises(A.AudioKVError) as e:
+            A.workspace_bytes(p, [2048])
+        assert e.value.code == code
+    with pytest.raises(A.AudioKVError) as e:
+        A.total_kept(good, [2048], 0.001)         # n_keep below the window
+    assert e.value.code == -1
+    with pytest.raises(A.AudioKVError) as e:
+        A.total_kept(good, [16], 0.5)             # L below the window
+    assert e.value.code == -1
+    with pytest.raises(A.AudioKVError) as e:
+        A.total_kept(good, [], 0.5)
+    assert e.value.code == -1
+    # a GPU entry point given NULL pointers returns before touching the device
+    lib = A.binding._lib
+    cp = good.c()
+    lens = (C.c_int32 * 1)(2048)
+    rc = lib.audiokv_score(C.byref(cp), None, None, None, lens, 1, None, None, 0, None)
+    assert rc == -1 and b"NULL" in lib.audiokv_last_error()
+    rc = lib.audiokv_evict(C.byref(cp), None, None, None, None, 1, None, lens, 1, 0.4, 0.125, 1.0,
+                           None, None, None, None, None, None, 0, None)
+    assert rc == -1
+    bad = A.Params(28, 4, 128, 32).c()
+    bad.size = 12
+    rc = lib.audiokv_score(C.byref(bad), None, None, None, lens, 1, None, None, 0, None)
+    assert rc == -1 and b"size" in lib.audiokv_last_error()
