@@ -113,7 +113,8 @@ Workspace plan_workspace(const audiokv_params* p, const Batch& b) {
     const int nsplit = score_num_splits(n_heads, b.max_L, rows, p->head_dim);
     size_t off = 0;
     w.stats_off = off;
-    off += align_up((size_t)n_heads * nsplit * (rows_pad > 0 ? rows_pad : 1) * 2 * sizeof(float), 256);
+    // partial row statistics [head][split][rows_pad][2], then the merged per-row constants [head][rows_pad]
+    off += align_up((size_t)n_heads * (rows_pad > 0 ? rows_pad : 1) * (2 * (size_t)nsplit + 1) * sizeof(float), 256);
     w.raw_off = off;
     off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
     w.smooth_off = off;

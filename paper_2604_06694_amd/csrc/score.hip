@@ -8,33 +8,24 @@ namespace {
 
 struct Plan { int NB, WR, rows_pad, tile_keys; };
 
-// Instantiated row-block counts per head_dim (must match score_d*.hip).
-const int kNB64[] = {1, 2, 4, 8};
-const int kNB128[] = {1, 2, 4, 7, 8};
-const int kNB256[] = {1, 2, 4};
+// Instantiated (32-row blocks per wave, waves per workgroup) pairs, by padded row count (must match score_d*.hip).
+struct Combo { int NB, WR; };
+const Combo kCombos128[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {2, 4}, {2, 7}, {2, 8}};   // d = 64, 128
+const Combo kCombos256[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {1, 8}};                   // d = 256
 
 bool make_plan(int rows, int D, Plan* out) {
-    const int* nbs; int n_nb;
-    if (D == 64) { nbs = kNB64; n_nb = 4; }
-    else if (D == 128) { nbs = kNB128; n_nb = 5; }
-    else if (D == 256) { nbs = kNB256; n_nb = 3; }
+    const Combo* cs; int n;
+    if (D == 64 || D == 128) { cs = kCombos128; n = 7; }
+    else if (D == 256) { cs = kCombos256; n = 5; }
     else return false;
-    bool found = false;
-    Plan best{};
-    for (int WR = 4; WR >= 2; WR >>= 1) {            // prefer more row-splitting waves on equal padding
-        for (int i = 0; i < n_nb; ++i) {
-            const int pad = nbs[i] * 16 * WR;
-            if (pad < rows) continue;
-            if (!found || pad < best.rows_pad) {
-                const int kb = (D == 256) ? 2 : 4;
-                best = Plan{nbs[i], WR, pad, 16 * kb * (4 / WR)};
-                found = true;
-            }
-            break;                                    // larger NB only pads more
+    for (int i = 0; i < n; ++i) {                     // sorted by padded rows: the first that fits pads least
+        const int pad = cs[i].NB * 32 * cs[i].WR;
+        if (pad >= rows) {
+            *out = Plan{cs[i].NB, cs[i].WR, pad, (D == 256) ? 32 : 64};
+            return true;
         }
     }
-    if (found) *out = best;
-    return found;
+    return false;
 }
 
 }  // namespace
@@ -47,13 +38,21 @@ int score_padded_rows(int rows, int D) {
 int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
     Plan p;
     if (!make_plan(rows, D, &p) || n_heads_total <= 0) return 1;
+    // A head is cut into key ranges so that the grid fills the 256 CUs in whole rounds: pick the split
+    // count that minimises rounds x (tiles per workgroup + fixed prologue cost, in tiles).
     const int tiles = (max_L + p.tile_keys - 1) / p.tile_keys;
-    const int target_groups = 1024;                   // ~4 workgroups per CU of a 256-CU part
-    int ns = (target_groups + n_heads_total - 1) / n_heads_total;
-    ns = ns < 1 ? 1 : ns;
-    ns = ns > 64 ? 64 : ns;
-    ns = ns > tiles ? tiles : ns;
-    return ns < 1 ? 1 : ns;
+    const int slots = 256 * (p.WR >= 7 ? 1 : 2);      // resident workgroups
+    const int overhead = 3;
+    int best = 1;
+    long long best_cost = -1;
+    const int ns_max = tiles < 64 ? tiles : 64;
+    for (int ns = 1; ns <= ns_max; ++ns) {
+        const long long groups = (long long)n_heads_total * ns;
+        const long long rounds = (groups + slots - 1) / slots;
+        const long long cost = rounds * ((tiles + ns - 1) / ns + overhead);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = ns; }
+    }
+    return best;
 }
 
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,

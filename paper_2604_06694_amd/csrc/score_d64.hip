@@ -1,4 +1,4 @@
-// Score kernels for head_dim = 64 (row-block counts instantiated: 1 2 4 8; row-splitting waves: 2 or 4).
+// Score kernels for head_dim = 64. Instantiated (32-row blocks per wave, waves per workgroup): 1,1 1,2 1,4 1,7 2,4 2,7 2,8.
 #include "score_impl.h"
 
 namespace audiokv {
@@ -7,14 +7,13 @@ hipError_t launch_score_d64(const Geom& g, int NB, int WR, const void* q_win, co
         const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between)
 {
     using namespace score_detail;
+    if (NB == 1 && WR == 1) return launch_both_sweeps<64, 1, 1>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
     if (NB == 1 && WR == 2) return launch_both_sweeps<64, 1, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
     if (NB == 1 && WR == 4) return launch_both_sweeps<64, 1, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 2 && WR == 2) return launch_both_sweeps<64, 2, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
+    if (NB == 1 && WR == 7) return launch_both_sweeps<64, 1, 7>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
     if (NB == 2 && WR == 4) return launch_both_sweeps<64, 2, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 4 && WR == 2) return launch_both_sweeps<64, 4, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 4 && WR == 4) return launch_both_sweeps<64, 4, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 8 && WR == 2) return launch_both_sweeps<64, 8, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 8 && WR == 4) return launch_both_sweeps<64, 8, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
+    if (NB == 2 && WR == 7) return launch_both_sweeps<64, 2, 7>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
+    if (NB == 2 && WR == 8) return launch_both_sweeps<64, 2, 8>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
     return hipErrorInvalidValue;
 }
 

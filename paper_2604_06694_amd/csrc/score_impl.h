@@ -5,26 +5,40 @@
 //               softmax_j(scale * <q_r, k_j>)
 //
 // The contraction (G*W rows) x (L keys) x d is dense, so it runs on bf16 MFMA
-// (v_mfma_f32_16x16x32_bf16, fp32 accumulate). A softmax row needs its max and
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulate). A softmax row needs its max and
 // its sum over ALL keys before any column sum can be formed, so the work is
-// two sweeps over K with the same tiling:
+// two sweeps over K with the same tiling, and a tiny merge in between:
 //   sweep 1: logits tile -> running (max, sum of exp) per row, per key range
+//   merge  : per row, max + log2(sum) over the key ranges
 //   sweep 2: logits tile -> exp2(z - max - log2 sum) summed over rows, per key
 // Keeping logits instead would cost G*W*4 bytes per token and head against the
 // d*2 bytes of the key itself, so recomputing is the cheaper choice.
 //
-// Tiling. A workgroup (4 waves) owns one KV head and a range of key tiles. The
-// window queries are the stationary MFMA operand: each wave keeps NB blocks of
-// 16 rows in registers for the whole kernel (WR waves split the rows, the
-// other 4/WR split the keys of a tile). K tiles are read from HBM once per
-// sweep with 16-byte coalesced loads, staged in LDS, and each wave pulls the
-// 16-key x 32-channel fragments it needs. Sweep 1 uses C = K Q^T (a lane owns
-// one query row, so max/sum stay in the lane); sweep 2 uses C = Q K^T (a lane
-// owns one key, so the column sum stays in the lane). Both orientations use
-// the same register fragments: only the operand order of the MFMA differs.
+// Both sweeps are bound by the vector ALU next to the matrix pipe: each logit
+// costs one MFMA-lane-slot plus (fma, exp2, add). The 32x32x16 shape is used
+// because one MFMA issue then covers twice as many logits as 16x16x32, which
+// leaves more issue slots in which the vector work of the previous block hides.
+//
+// Tiling. A workgroup of WR compute waves plus one loader wave owns one KV head
+// and a range of key tiles. The window queries are the stationary MFMA operand:
+// compute wave w keeps rows [w*NB*32, (w+1)*NB*32) as register fragments for
+// the whole kernel. K tiles (64 keys, or 32 at d = 256) are read from HBM once
+// per sweep by the loader wave (16-byte coalesced loads, two tiles ahead of the
+// compute waves, through a ring of three LDS buffers, one barrier per tile), so
+// the HBM latency is paid by a wave that has nothing else to do and the compute
+// waves hold no staging registers. Every compute wave pulls all 32-key x
+// 16-channel fragments of the tile. Sweep 1 computes
+// C = K Q^T (a lane owns one query row, so max/sum stay in the lane); sweep 2
+// computes C = Q K^T (a lane owns one key, so the column sum stays in the
+// lane). Both orientations use the same register fragments: only the operand
+// order of the MFMA differs. Only the last tiles of a head contain keys that
+// some window row may not see; they take a separate, masked instantiation of
+// the tile body so that the common path carries no compare/select work.
 //
 // Everything is in base-2 units: z2 = <q,k> * scale * log2(e).
 #pragma once
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -33,23 +47,24 @@ namespace score_detail {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-constexpr int kThreads = 256;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 template <int D, int NB, int WR>
 struct Tile {
-    static constexpr int WK = 4 / WR;                 // waves splitting the keys of a tile
-    static constexpr int KB = (D == 256) ? 2 : 4;     // 16-key blocks per wave per tile
-    static constexpr int KW = 16 * KB;                // keys per wave per tile
-    static constexpr int TK = KW * WK;                // keys per workgroup tile
-    static constexpr int KK = D / 32;                 // MFMA k-steps per logit
-    static constexpr int ROWS = NB * 16 * WR;         // padded window rows per head
-    static constexpr int ROW_BYTES = D * 2 + 16;      // LDS row pitch (16 B pad: conflict-free fragment reads)
+    static constexpr int THREADS = 64 * (WR + 1);      // WR compute waves + 1 loader wave
+    static constexpr int KB = (D == 256) ? 1 : 2;     // 32-key blocks per tile
+    static constexpr int TK = 32 * KB;                // keys per tile
+    static constexpr int KK = D / 16;                 // MFMA k-steps per logit
+    static constexpr int ROWS = NB * 32 * WR;         // padded window rows per head
+    static constexpr int ROW_BYTES = D * 2 + 16;      // LDS row pitch (16 B pad spreads the fragment reads over the banks)
     static constexpr int CHUNKS = TK * D / 8;         // 16-byte pieces per tile
-    static constexpr int CH = CHUNKS / kThreads;      // pieces per thread
-    static_assert(CHUNKS % kThreads == 0, "tile must split evenly over the workgroup");
-    static constexpr int LDS_K = TK * ROW_BYTES;
-    static constexpr int LDS_BYTES = LDS_K + ROWS * 8 + WR * TK * 4;
+    static constexpr int CH = CHUNKS / 64;            // pieces per lane of the loader wave
+    static_assert(CHUNKS % 64 == 0, "a tile is a whole number of wave-wide 16-byte loads");
+    static constexpr int STAGES = 3;                  // LDS ring: loader runs two tiles ahead
+    static constexpr int LDS_K = TK * ROW_BYTES;      // one K buffer
+    static constexpr int LDS_COLS = WR * TK * 4;      // one column-sum exchange buffer
+    static constexpr int LDS_RC = ROWS * 4;           // sweep 2: per-row normalisation constants
+    static constexpr int LDS_BYTES = STAGES * LDS_K + 2 * LDS_COLS + LDS_RC;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -62,18 +77,26 @@ __device__ __forceinline__ void merge_stats(float& m, float& l, float m2, float 
     m = M;
 }
 
+// last key index that window row r may attend to (-1: padded row, sees nothing)
+__device__ __forceinline__ int last_visible(const Geom& g, int L, int R, int r) {
+    return (r < R) ? (g.causal ? (L - g.W + (r % g.W)) : (L - 1)) : -1;
+}
+
+// Row (sweep 2) or key (sweep 1) offset inside a 32x32 MFMA result block of element i (0..15) for lane half g2.
+__device__ __forceinline__ constexpr int c_row(int i, int g2) { return (i >> 2) * 8 + g2 * 4 + (i & 3); }
+
 template <int D, int NB, int WR, bool SWEEP2>
-__global__ __launch_bounds__(kThreads) void score_kernel(
+__global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     Geom g, const __bf16* __restrict__ q_win, const __bf16* __restrict__ k,
     const int32_t* __restrict__ cu_seq, int nsplit,
-    float* __restrict__ stats,      // [head][split][ROWS][2] : (max in base-2 units, sum of exp2)
-    float* __restrict__ raw)        // sweep 2 output, packed like scores
+    float* __restrict__ stats,        // sweep 1 out: [head][split][ROWS][2] = (max in base-2 units, sum of exp2)
+    const float* __restrict__ cst,    // sweep 2 in : [head][ROWS] = max + log2(sum), +inf for padded rows
+    float* __restrict__ raw)          // sweep 2 out, packed like scores
 {
     using T = Tile<D, NB, WR>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    unsigned char* lds_k = lds;
-    float* lds_rows = reinterpret_cast<float*>(lds + T::LDS_K);            // ROWS * 2 floats
-    float* lds_cols = lds_rows + T::ROWS * 2;                              // WR * TK floats
+    float* lds_cols = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K);
+    float* lds_rc = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K + 2 * T::LDS_COLS);
 
     const int head = blockIdx.x / nsplit;
     const int split = blockIdx.x - head * nsplit;
@@ -85,227 +108,250 @@ __global__ __launch_bounds__(kThreads) void score_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wr = wave % WR, wk = wave / WR;
-    const int l16 = lane & 15, lg = lane >> 4;
-    const int row0 = wr * NB * 16;
+    const int l32 = lane & 31, g2 = lane >> 5;
+    const int row0 = wave * NB * 32;
 
     const int n_tiles = (L + T::TK - 1) / T::TK;
     const int tps = (n_tiles + nsplit - 1) / nsplit;
     const int t_begin = split * tps;
     const int t_end = min(n_tiles, t_begin + tps);
-    float* my_stats = stats + ((size_t)head * nsplit + split) * T::ROWS * 2;
 
     if (t_begin >= t_end) {                           // uniform over the workgroup
-        if (!SWEEP2)
-            for (int r = tid; r < T::ROWS; r += kThreads) { my_stats[2 * r] = -INFINITY; my_stats[2 * r + 1] = 0.f; }
+        if (!SWEEP2) {
+            float* my_stats = stats + ((size_t)head * nsplit + split) * T::ROWS * 2;
+            for (int r = tid; r < T::ROWS; r += T::THREADS) { my_stats[2 * r] = -INFINITY; my_stats[2 * r + 1] = 0.f; }
+        }
         return;
     }
 
-    // ---- stationary operand: this wave's window queries, as MFMA fragments --------------------
-    // fragment (rb, kk): lane holds row rb*16 + l16, channels kk*32 + lg*8 .. +8
+    // sweep 2: add the WR waves' partial column sums of the tile starting at j0 (fixed order) and store them
+    auto flush_cols = [&](int buf, int j0) {
+        if (lane < T::TK && j0 + lane < L) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < WR; ++w) v += lds_cols[buf * (WR * T::TK) + w * T::TK + lane];
+            raw[(size_t)tok0 * g.H_kv + (size_t)h * L + j0 + lane] = v;
+        }
+    };
+
+    if (wave == WR) {
+        // ================= loader wave: HBM -> registers -> LDS ring, two tiles ahead =================
+        // Rows past the end are clamped to the last row, never zero-filled: every tile that reaches past
+        // L - W is a masked tile, and the masked path discards those logits.
+        // piece `it` of a tile is its 16-byte chunk it*64 + lane: a wave-wide load covers 1 KiB of consecutive rows
+        int piece_row[T::CH], piece_lds[T::CH];
+#pragma unroll
+        for (int it = 0; it < T::CH; ++it) {
+            const int cidx = it * 64 + lane;
+            piece_row[it] = cidx / (D / 8);
+            piece_lds[it] = piece_row[it] * T::ROW_BYTES + (cidx - piece_row[it] * (D / 8)) * 16;
+        }
+        const int part8 = (lane % (D / 8)) * 8;         // channel offset of this lane's chunk (same for all pieces)
+        uint4 stage[T::CH];
+#define AUDIOKV_FETCH(t_)                                                                                    \
+        _Pragma("unroll") for (int it = 0; it < T::CH; ++it) {                                               \
+            const int j_ = min((t_) * T::TK + piece_row[it], L - 1);                                         \
+            stage[it] = *reinterpret_cast<const uint4*>(k + kv_row_offset(g, tok0, L, h, j_) + part8);       \
+        }
+#define AUDIOKV_DEPOSIT(slot_)                                                                               \
+        _Pragma("unroll") for (int it = 0; it < T::CH; ++it)                                                 \
+            *reinterpret_cast<uint4*>(lds + (slot_) * T::LDS_K + piece_lds[it]) = stage[it];
+        AUDIOKV_FETCH(t_begin)
+        AUDIOKV_DEPOSIT(0)
+        if (t_begin + 1 < t_end) {
+            AUDIOKV_FETCH(t_begin + 1)
+            AUDIOKV_DEPOSIT(1)
+        }
+        __syncthreads();
+        int slot_w = 2;                                 // ring slot of tile t + 2
+        for (int t = t_begin; t < t_end; ++t) {
+            // unconditional (past the end it re-reads the last tile into a slot nobody reads again)
+            if (SWEEP2 && t > t_begin) flush_cols((t - 1 - t_begin) & 1, (t - 1) * T::TK);
+            AUDIOKV_FETCH(min(t + 2, t_end - 1))
+            AUDIOKV_DEPOSIT(slot_w)                     // that slot was last read in iteration t - 1, which ended with a barrier
+            slot_w = (slot_w == T::STAGES - 1) ? 0 : slot_w + 1;
+            __syncthreads();
+        }
+#undef AUDIOKV_FETCH
+#undef AUDIOKV_DEPOSIT
+        if (SWEEP2) flush_cols((t_end - 1 - t_begin) & 1, (t_end - 1) * T::TK);
+        return;
+    }
+
+    // ================= compute waves =================
+    // stationary operand: this wave's window queries, as MFMA fragments
+    // fragment (rb, kk): lane holds row row0 + rb*32 + l32, channels kk*16 + g2*8 .. +8
     bf16x8 qf[NB][T::KK];
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) {
-        const int r = row0 + rb * 16 + l16;
+        const int r = row0 + rb * 32 + l32;
         const bool live = r < R;
         const int qh = live ? r / g.W : 0, wrow = live ? r - qh * g.W : 0;
-        const __bf16* src = q_win + (((size_t)item * g.H_q + (size_t)h * g.G + qh) * g.W + wrow) * D + lg * 8;
+        const __bf16* src = q_win + (((size_t)item * g.H_q + (size_t)h * g.G + qh) * g.W + wrow) * D + g2 * 8;
 #pragma unroll
         for (int kk = 0; kk < T::KK; ++kk) {
             bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (live) v = *reinterpret_cast<const bf16x8*>(src + kk * 32);
+            if (live) v = *reinterpret_cast<const bf16x8*>(src + kk * 16);
             qf[rb][kk] = v;
         }
     }
+    if (SWEEP2)
+        for (int r = tid; r < T::ROWS; r += 64 * WR) lds_rc[r] = cst[(size_t)head * T::ROWS + r];
 
-    // ---- sweep 2 needs each row's final max + log2(sum): merge the per-range partials -----------
-    if (SWEEP2) {
-        const float* hs = stats + (size_t)head * nsplit * T::ROWS * 2;
-        for (int r = tid; r < T::ROWS; r += kThreads) {
-            float cst = INFINITY;                     // padded rows: exp2(z - inf) = 0, they add nothing
-            if (r < R) {
-                float M = -INFINITY;
-                for (int s = 0; s < nsplit; ++s) M = fmaxf(M, hs[((size_t)s * T::ROWS + r) * 2]);
-                float Z = 0.f;
-                for (int s = 0; s < nsplit; ++s) {
-                    const float ms = hs[((size_t)s * T::ROWS + r) * 2], ls = hs[((size_t)s * T::ROWS + r) * 2 + 1];
-                    if (ls > 0.f) Z += ls * fast_exp2(ms - M);
-                }
-                cst = M + __log2f(Z);
-            }
-            lds_rows[r] = cst;
-        }
-    }
-
-    // sweep 1 state: running max (raw logit units) and sum for row rb*16 + l16, over this lane's keys
+    // sweep 1: running max (raw logit units) and sum for row row0 + rb*32 + l32 over this lane's keys
     float run_m[NB], run_l[NB];
-    int last_vis[NB];                                  // last key index the lane's row may see (sweep 1)
 #pragma unroll
-    for (int rb = 0; rb < NB; ++rb) {
-        run_m[rb] = -INFINITY;
-        run_l[rb] = 0.f;
-        const int r = row0 + rb * 16 + l16;
-        last_vis[rb] = (r < R) ? (g.causal ? (L - g.W + (r % g.W)) : (L - 1)) : -1;
-    }
+    for (int rb = 0; rb < NB; ++rb) { run_m[rb] = -INFINITY; run_l[rb] = 0.f; }
 
-    // ---- K tile staging: global -> registers (next tile) -> LDS -> MFMA fragments ----------------
-    uint4 stage[T::CH];
-    auto load_tile = [&](int t) {
-        const int j0 = t * T::TK;
+    // one tile: all logits of (this wave's rows) x (the tile's keys), then the sweep's reduction.
+    // K fragments are pulled from LDS one k-step ahead of the MFMAs that use them (two register slots),
+    // so only the accumulators of the NB x KB result blocks stay live through the tile.
+    auto tile_body = [&](auto masked_tag, int slot, int cbuf, int j0) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const unsigned char* kbase = lds + slot * T::LDS_K + l32 * T::ROW_BYTES + g2 * 16;
+        auto frag = [&](int kb, int kk) {              // key kb*32 + l32, channels kk*16 + g2*8 .. +8
+            return *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * T::ROW_BYTES + kk * 32);
+        };
+        f32x16 acc[NB][T::KB];
+        bf16x8 kf[2][T::KB];
 #pragma unroll
-        for (int it = 0; it < T::CH; ++it) {
-            const int cidx = tid + it * kThreads;
-            const int key = cidx / (D / 8), part = cidx - key * (D / 8);
-            const int j = j0 + key;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (j < L) v = *reinterpret_cast<const uint4*>(k + kv_row_offset(g, tok0, L, h, j) + part * 8);
-            stage[it] = v;
+        for (int kb = 0; kb < T::KB; ++kb) kf[0][kb] = frag(kb, 0);
+#pragma unroll
+        for (int kk = 0; kk < T::KK; ++kk) {
+            if (kk + 1 < T::KK) {
+#pragma unroll
+                for (int kb = 0; kb < T::KB; ++kb) kf[(kk + 1) & 1][kb] = frag(kb, kk + 1);
+            }
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int kb = 0; kb < T::KB; ++kb) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    const f32x16 cin = (kk == 0) ? zero : acc[rb][kb];
+                    if (SWEEP2)   // C[row][key]: lane = key l32, rows c_row(i, g2)
+                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf[kk & 1][kb], cin, 0, 0, 0);
+                    else          // C[key][row]: lane = row l32, keys c_row(i, g2)
+                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][kb], qf[rb][kk], cin, 0, 0, 0);
+                }
         }
-    };
-    load_tile(t_begin);
 
-    for (int t = t_begin; t < t_end; ++t) {
-        const int j0 = t * T::TK;
+        float colsum[T::KB][2];
 #pragma unroll
-        for (int it = 0; it < T::CH; ++it) {
-            const int cidx = tid + it * kThreads;
-            const int key = cidx / (D / 8), part = cidx - key * (D / 8);
-            *reinterpret_cast<uint4*>(lds_k + key * T::ROW_BYTES + part * 16) = stage[it];
-        }
-        __syncthreads();
-
-        bf16x8 kf[T::KB][T::KK];                       // fragment: key kb*16 + l16, channels kk*32 + lg*8 .. +8
+        for (int kb = 0; kb < T::KB; ++kb) colsum[kb][0] = colsum[kb][1] = 0.f;
+        // The row constants are re-read from LDS in every tile. Passing their offset through an empty asm keeps
+        // the compiler from proving the reads tile-invariant and hoisting all of them (32 registers) out of the loop.
+        int rc_off = row0 + g2 * 4;
+        asm volatile("" : "+v"(rc_off));
 #pragma unroll
-        for (int kb = 0; kb < T::KB; ++kb)
-#pragma unroll
-            for (int kk = 0; kk < T::KK; ++kk)
-                kf[kb][kk] = *reinterpret_cast<const bf16x8*>(
-                    lds_k + (wk * T::KW + kb * 16 + l16) * T::ROW_BYTES + (kk * 32 + lg * 8) * 2);
-
-        if (t + 1 < t_end) load_tile(t + 1);           // in flight while this tile is computed
-        __syncthreads();                               // every wave holds its fragments: the LDS tile is free
-
-        const int jw0 = j0 + wk * T::KW;               // first key of this wave's part of the tile
-        // does any (row, key) pair of this tile need the visibility test?
-        const bool masked = g.causal ? (j0 + T::TK - 1 > L - g.W) : (j0 + T::TK > L);
-
-        if (!SWEEP2) {
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                f32x4 acc[T::KB];
-#pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb) acc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < T::KK; ++kk)
-#pragma unroll
-                    for (int kb = 0; kb < T::KB; ++kb)    // C[key][row]: lane = row l16, keys 4*lg + i
-                        acc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][kk], qf[rb][kk], acc[kb], 0, 0, 0);
-                if (masked) {
+        for (int rb = 0; rb < NB; ++rb) {
+            if (!SWEEP2) {
+                if (MASKED) {
+                    const int lv = last_visible(g, L, R, row0 + rb * 32 + l32);
 #pragma unroll
                     for (int kb = 0; kb < T::KB; ++kb)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (jw0 + kb * 16 + 4 * lg + i > last_vis[rb]) acc[kb][i] = -INFINITY;
+                        for (int i = 0; i < 16; ++i)
+                            if (j0 + kb * 32 + c_row(i, g2) > lv) acc[rb][kb][i] = -INFINITY;
                 }
                 float mx = -INFINITY;
 #pragma unroll
                 for (int kb = 0; kb < T::KB; ++kb)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, acc[kb][i]);
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][kb][i]);
                 const float m_new = fmaxf(run_m[rb], mx);
                 const float ms = (m_new == -INFINITY) ? 0.f : m_new;
                 const float msc = ms * c;
-                float sum = 0.f;
+                float s0 = 0.f, s1 = 0.f;
 #pragma unroll
                 for (int kb = 0; kb < T::KB; ++kb)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) sum += fast_exp2(fmaf(acc[kb][i], c, -msc));
-                run_l[rb] = run_l[rb] * fast_exp2((run_m[rb] - ms) * c) + sum;
+                    for (int i = 0; i < 16; i += 2) {
+                        s0 += fast_exp2(fmaf(acc[rb][kb][i], c, -msc));
+                        s1 += fast_exp2(fmaf(acc[rb][kb][i + 1], c, -msc));
+                    }
+                run_l[rb] = run_l[rb] * fast_exp2((run_m[rb] - ms) * c) + (s0 + s1);
                 run_m[rb] = m_new;
-            }
-        } else {
-            float colsum[T::KB];
+            } else {
+                if (MASKED) {
 #pragma unroll
-            for (int kb = 0; kb < T::KB; ++kb) colsum[kb] = 0.f;
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                f32x4 acc[T::KB];
-#pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb) acc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < T::KK; ++kk)
-#pragma unroll
-                    for (int kb = 0; kb < T::KB; ++kb)    // C[row][key]: lane = key l16, rows 4*lg + i
-                        acc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[rb][kk], kf[kb][kk], acc[kb], 0, 0, 0);
-                const f32x4 cst = *reinterpret_cast<const f32x4*>(lds_rows + row0 + rb * 16 + 4 * lg);
-                if (masked) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int r = row0 + rb * 16 + 4 * lg + i;
-                        const int lv = (r < R) ? (g.causal ? (L - g.W + (r % g.W)) : (L - 1)) : -1;
+                    for (int i = 0; i < 16; ++i) {
+                        const int lv = last_visible(g, L, R, row0 + rb * 32 + c_row(i, g2));
 #pragma unroll
                         for (int kb = 0; kb < T::KB; ++kb)
-                            if (jw0 + kb * 16 + l16 > lv) acc[kb][i] = -INFINITY;
+                            if (j0 + kb * 32 + l32 > lv) acc[rb][kb][i] = -INFINITY;
                     }
                 }
 #pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb)
+                for (int q4 = 0; q4 < 4; ++q4) {           // rows 8*q4 + 4*g2 + {0..3}: one 16-byte read
+                    const f32x4 rc = *reinterpret_cast<const f32x4*>(lds_rc + rc_off + rb * 32 + q4 * 8);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) colsum[kb] += fast_exp2(fmaf(acc[kb][i], c, -cst[i]));
-            }
-            // rows of the other lane groups, then rows of the other waves (fixed order: deterministic)
-#pragma unroll
-            for (int kb = 0; kb < T::KB; ++kb) {
-                float v = colsum[kb];
-                v += __shfl_xor(v, 16, 64);
-                v += __shfl_xor(v, 32, 64);
-                if (lg == 0) lds_cols[wr * T::TK + wk * T::KW + kb * 16 + l16] = v;
-            }
-            __syncthreads();
-            if (tid < T::TK && j0 + tid < L) {
-                float v = 0.f;
-#pragma unroll
-                for (int w = 0; w < WR; ++w) v += lds_cols[w * T::TK + tid];
-                raw[(size_t)tok0 * g.H_kv + (size_t)h * L + j0 + tid] = v;
+                    for (int kb = 0; kb < T::KB; ++kb) {
+                        colsum[kb][0] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 0], c, -rc[0]));
+                        colsum[kb][1] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 1], c, -rc[1]));
+                        colsum[kb][0] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 2], c, -rc[2]));
+                        colsum[kb][1] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 3], c, -rc[3]));
+                    }
+                }
             }
         }
+        if (SWEEP2) {
+            // rows held by the other half of the wave; the other waves' rows are added by the loader wave
+#pragma unroll
+            for (int kb = 0; kb < T::KB; ++kb) {
+                float v = colsum[kb][0] + colsum[kb][1];
+                v += __shfl_xor(v, 32, 64);
+                if (g2 == 0) lds_cols[cbuf * (WR * T::TK) + wave * T::TK + kb * 32 + l32] = v;
+            }
+        }
+    };
+
+    __syncthreads();                                    // tiles t_begin (and t_begin + 1) are in the ring
+    int slot_r = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        const int j0 = t * T::TK;
+        // does any (row, key) pair of this tile need the visibility test?
+        const bool masked = g.causal ? (j0 + T::TK - 1 > L - g.W) : (j0 + T::TK > L);
+        if (masked) tile_body(std::true_type{}, slot_r, (t - t_begin) & 1, j0);
+        else        tile_body(std::false_type{}, slot_r, (t - t_begin) & 1, j0);
+        slot_r = (slot_r == T::STAGES - 1) ? 0 : slot_r + 1;
+        __syncthreads();
     }
 
     if (!SWEEP2) {
-        // a row's keys are spread over the 4 lane groups of a wave and over the WK key-splitting waves
+        // a row's keys are spread over the two halves of the wave
+        float* my_stats = stats + ((size_t)head * nsplit + split) * T::ROWS * 2;
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) {
-#pragma unroll
-            for (int o = 16; o <= 32; o <<= 1) {
-                const float m2 = __shfl_xor(run_m[rb], o, 64), l2 = __shfl_xor(run_l[rb], o, 64);
-                merge_stats(run_m[rb], run_l[rb], m2, l2, c);
-            }
-        }
-        if (T::WK == 2) {
-            __syncthreads();                            // lds_rows is not in use by anyone in sweep 1
-            if (wk == 1 && lg == 0) {
-#pragma unroll
-                for (int rb = 0; rb < NB; ++rb) {
-                    lds_rows[2 * (row0 + rb * 16 + l16)] = run_m[rb];
-                    lds_rows[2 * (row0 + rb * 16 + l16) + 1] = run_l[rb];
-                }
-            }
-            __syncthreads();
-            if (wk == 0 && lg == 0) {
-#pragma unroll
-                for (int rb = 0; rb < NB; ++rb)
-                    merge_stats(run_m[rb], run_l[rb], lds_rows[2 * (row0 + rb * 16 + l16)],
-                                lds_rows[2 * (row0 + rb * 16 + l16) + 1], c);
-            }
-        }
-        if (wk == 0 && lg == 0) {
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                const int r = row0 + rb * 16 + l16;
+            const float m2 = __shfl_xor(run_m[rb], 32, 64), l2 = __shfl_xor(run_l[rb], 32, 64);
+            merge_stats(run_m[rb], run_l[rb], m2, l2, c);
+            if (g2 == 0) {
+                const int r = row0 + rb * 32 + l32;
                 my_stats[2 * r] = (run_m[rb] == -INFINITY) ? -INFINITY : run_m[rb] * c;
                 my_stats[2 * r + 1] = run_l[rb];
             }
         }
+    }
+}
+
+// per row: max + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes
+static __global__ __launch_bounds__(256) void score_merge_kernel(const float* __restrict__ stats, int nsplit,
+                                                                 int rows_pad, int R, float* __restrict__ cst)
+{
+    const int head = blockIdx.x;
+    const float* hs = stats + (size_t)head * nsplit * rows_pad * 2;
+    for (int r = threadIdx.x; r < rows_pad; r += blockDim.x) {
+        float out = INFINITY;
+        if (r < R) {
+            float M = -INFINITY;
+            for (int s = 0; s < nsplit; ++s) M = fmaxf(M, hs[((size_t)s * rows_pad + r) * 2]);
+            float Z = 0.f;
+            for (int s = 0; s < nsplit; ++s) {
+                const float ms = hs[((size_t)s * rows_pad + r) * 2], ls = hs[((size_t)s * rows_pad + r) * 2 + 1];
+                if (ls > 0.f) Z += ls * fast_exp2(ms - M);
+            }
+            out = M + __log2f(Z);
+        }
+        cst[(size_t)head * rows_pad + r] = out;
     }
 }
 
@@ -316,6 +362,7 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
     using T = Tile<D, NB, WR>;
     const int n_heads = g.n_items * g.H_kv;
     const dim3 grid((unsigned)(n_heads * nsplit));
+    float* cst = stats + (size_t)n_heads * nsplit * T::ROWS * 2;
     static bool attr_set = false;
     if (!attr_set && T::LDS_BYTES > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<D, NB, WR, false>),
@@ -326,14 +373,16 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(kThreads), T::LDS_BYTES, s, g,
-                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, raw);
+    hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
+                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, (const float*)nullptr, raw);
+    hipLaunchKernelGGL(score_merge_kernel, dim3(n_heads), dim3(256), 0, s, (const float*)stats, nsplit, T::ROWS,
+                       g.G * g.W, cst);
     if (between) {
         const hipError_t e = hipEventRecord(between, s);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(kThreads), T::LDS_BYTES, s, g,
-                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, raw);
+    hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
+                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, (float*)nullptr, (const float*)cst, raw);
     return hipGetLastError();
 }
 
