@@ -19,7 +19,7 @@ LIB = os.path.join(PKG_DIR, "libaudiokv.so")
 
 ARCH = "gfx950"
 COMMON = [
-    "hipcc", f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC",
+    "hipcc", f"--offload-arch={ARCH}", "-O3", "-std=c++20", "-fPIC",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
     # packed-fp32 instruction forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -39,6 +39,7 @@
 #pragma once
 
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 
@@ -64,7 +65,7 @@ struct Tile {
     static constexpr int LDS_K = TK * ROW_BYTES;      // one K buffer
     static constexpr int LDS_COLS = WR * TK * 4;      // one column-sum exchange buffer
     static constexpr int LDS_RC = ROWS * 4;           // sweep 2: per-row normalisation constants
-    static constexpr int LDS_BYTES = STAGES * LDS_K + 2 * LDS_COLS + LDS_RC;
+    static constexpr int LDS_BYTES = STAGES * LDS_K + 3 * LDS_COLS + LDS_RC;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     using T = Tile<D, NB, WR>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     float* lds_cols = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K);
-    float* lds_rc = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K + 2 * T::LDS_COLS);
+    float* lds_rc = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K + 3 * T::LDS_COLS);
 
     const int head = blockIdx.x / nsplit;
     const int split = blockIdx.x - head * nsplit;
@@ -147,34 +148,36 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
             piece_lds[it] = piece_row[it] * T::ROW_BYTES + (cidx - piece_row[it] * (D / 8)) * 16;
         }
         const int part8 = (lane % (D / 8)) * 8;         // channel offset of this lane's chunk (same for all pieces)
+        // The staged tile is carried in registers from one iteration to the next. Fold expressions give straight-line
+        // code per piece, so the array is split into scalars before any loop transformation can get in the way.
         uint4 stage[T::CH];
-#define AUDIOKV_FETCH(t_)                                                                                    \
-        _Pragma("unroll") for (int it = 0; it < T::CH; ++it) {                                               \
-            const int j_ = min((t_) * T::TK + piece_row[it], L - 1);                                         \
-            stage[it] = *reinterpret_cast<const uint4*>(k + kv_row_offset(g, tok0, L, h, j_) + part8);       \
-        }
-#define AUDIOKV_DEPOSIT(slot_)                                                                               \
-        _Pragma("unroll") for (int it = 0; it < T::CH; ++it)                                                 \
-            *reinterpret_cast<uint4*>(lds + (slot_) * T::LDS_K + piece_lds[it]) = stage[it];
+        auto fetch_one = [&](int it, int t_) {
+            const int j_ = min(t_ * T::TK + piece_row[it], L - 1);
+            return *reinterpret_cast<const uint4*>(k + kv_row_offset(g, tok0, L, h, j_) + part8);
+        };
+#define AUDIOKV_FETCH(t_)    { const int tt_ = (t_); [&]<size_t... I>(std::index_sequence<I...>) { ((stage[I] = fetch_one((int)I, tt_)), ...); }(std::make_index_sequence<T::CH>{}); }
+#define AUDIOKV_DEPOSIT(s_)  { const int ss_ = (s_); [&]<size_t... I>(std::index_sequence<I...>) { ((*reinterpret_cast<uint4*>(lds + ss_ * T::LDS_K + piece_lds[I]) = stage[I]), ...); }(std::make_index_sequence<T::CH>{}); }
         AUDIOKV_FETCH(t_begin)
         AUDIOKV_DEPOSIT(0)
-        if (t_begin + 1 < t_end) {
-            AUDIOKV_FETCH(t_begin + 1)
-            AUDIOKV_DEPOSIT(1)
-        }
+        AUDIOKV_FETCH(min(t_begin + 1, t_end - 1))
+        AUDIOKV_DEPOSIT(1)
+        AUDIOKV_FETCH(min(t_begin + 2, t_end - 1))       // stays in registers until the first loop iteration
         __syncthreads();
         int slot_w = 2;                                 // ring slot of tile t + 2
-        for (int t = t_begin; t < t_end; ++t) {
-            // unconditional (past the end it re-reads the last tile into a slot nobody reads again)
-            if (SWEEP2 && t > t_begin) flush_cols((t - 1 - t_begin) & 1, (t - 1) * T::TK);
-            AUDIOKV_FETCH(min(t + 2, t_end - 1))
-            AUDIOKV_DEPOSIT(slot_w)                     // that slot was last read in iteration t - 1, which ended with a barrier
+        for (int t = t_begin; t <= t_end; ++t) {        // one drain iteration more than there are tiles
+            // tile t + 2 was fetched during the previous iteration: its HBM latency hid behind a whole tile of
+            // compute. Its slot was last read in iteration t - 1, which ended with a barrier.
+            AUDIOKV_DEPOSIT(slot_w)
             slot_w = (slot_w == T::STAGES - 1) ? 0 : slot_w + 1;
+            // unconditional (past the end it re-reads the last tile into a slot nobody reads again)
+            AUDIOKV_FETCH(min(t + 3, t_end - 1))
+            // column sums of tile t - 2 are complete: half of the waves wrote them one iteration late
+            if (SWEEP2 && t - 2 >= t_begin) flush_cols((t - 2 - t_begin) % 3, (t - 2) * T::TK);
             __syncthreads();
         }
+        if (SWEEP2) flush_cols((t_end - 1 - t_begin) % 3, (t_end - 1) * T::TK);
 #undef AUDIOKV_FETCH
 #undef AUDIOKV_DEPOSIT
-        if (SWEEP2) flush_cols((t_end - 1 - t_begin) & 1, (t_end - 1) * T::TK);
         return;
     }
 
@@ -203,16 +206,18 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) { run_m[rb] = -INFINITY; run_l[rb] = 0.f; }
 
-    // one tile: all logits of (this wave's rows) x (the tile's keys), then the sweep's reduction.
-    // K fragments are pulled from LDS one k-step ahead of the MFMAs that use them (two register slots),
-    // so only the accumulators of the NB x KB result blocks stay live through the tile.
-    auto tile_body = [&](auto masked_tag, int slot, int cbuf, int j0) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
+    // One tile = an MFMA phase (all logits of this wave's rows x the tile's keys) and a reduction phase (the
+    // sweep's exp2 / sums on those logits). The matrix pipe and the vector ALU of a SIMD are shared by the two
+    // waves that live on it, and a barrier per tile keeps them in step, so both would run their MFMA phases
+    // together and then their reductions together. Waves 4.. therefore run their reduction one tile late
+    // (reduce(t-1), then mfma(t)): on every SIMD one wave is in the matrix pipe while the other is in the ALU.
+    // K fragments are pulled from LDS one k-step ahead of the MFMAs that use them (two register slots).
+    f32x16 acc[NB][T::KB];
+    auto mfma_phase = [&](int slot) {
         const unsigned char* kbase = lds + slot * T::LDS_K + l32 * T::ROW_BYTES + g2 * 16;
         auto frag = [&](int kb, int kk) {              // key kb*32 + l32, channels kk*16 + g2*8 .. +8
             return *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * T::ROW_BYTES + kk * 32);
         };
-        f32x16 acc[NB][T::KB];
         bf16x8 kf[2][T::KB];
 #pragma unroll
         for (int kb = 0; kb < T::KB; ++kb) kf[0][kb] = frag(kb, 0);
@@ -234,7 +239,9 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
                         acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][kb], qf[rb][kk], cin, 0, 0, 0);
                 }
         }
-
+    };
+    auto reduce_phase = [&](auto masked_tag, int cbuf, int j0) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         float colsum[T::KB][2];
 #pragma unroll
         for (int kb = 0; kb < T::KB; ++kb) colsum[kb][0] = colsum[kb][1] = 0.f;
@@ -304,15 +311,28 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
             }
         }
     };
-
-    __syncthreads();                                    // tiles t_begin (and t_begin + 1) are in the ring
-    int slot_r = 0;
-    for (int t = t_begin; t < t_end; ++t) {
+    // does any (row, key) pair of tile t need the visibility test?
+    auto is_masked = [&](int t) {
         const int j0 = t * T::TK;
-        // does any (row, key) pair of this tile need the visibility test?
-        const bool masked = g.causal ? (j0 + T::TK - 1 > L - g.W) : (j0 + T::TK > L);
-        if (masked) tile_body(std::true_type{}, slot_r, (t - t_begin) & 1, j0);
-        else        tile_body(std::false_type{}, slot_r, (t - t_begin) & 1, j0);
+        return g.causal ? (j0 + T::TK - 1 > L - g.W) : (j0 + T::TK > L);
+    };
+    auto reduce_tile = [&](int t) {
+        const int cbuf = (t - t_begin) % 3;
+        if (is_masked(t)) reduce_phase(std::true_type{}, cbuf, t * T::TK);
+        else              reduce_phase(std::false_type{}, cbuf, t * T::TK);
+    };
+
+    const bool late = wave >= 4;                        // shares its SIMD with wave - 4
+    __syncthreads();                                    // the first tiles are in the ring
+    int slot_r = 0;
+    for (int t = t_begin; t <= t_end; ++t) {            // one drain iteration, like the loader wave
+        if (late) {
+            if (t > t_begin) reduce_tile(t - 1);
+            if (t < t_end) mfma_phase(slot_r);
+        } else if (t < t_end) {
+            mfma_phase(slot_r);
+            reduce_tile(t);
+        }
         slot_r = (slot_r == T::STAGES - 1) ? 0 : slot_r + 1;
         __syncthreads();
     }
