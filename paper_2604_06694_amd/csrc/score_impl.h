@@ -213,20 +213,23 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     // (reduce(t-1), then mfma(t)): on every SIMD one wave is in the matrix pipe while the other is in the ALU.
     // K fragments are pulled from LDS one k-step ahead of the MFMAs that use them (two register slots).
     f32x16 acc[NB][T::KB];
-    auto mfma_phase = [&](int slot) {
-        const unsigned char* kbase = lds + slot * T::LDS_K + l32 * T::ROW_BYTES + g2 * 16;
-        auto frag = [&](int kb, int kk) {              // key kb*32 + l32, channels kk*16 + g2*8 .. +8
-            return *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * T::ROW_BYTES + kk * 32);
-        };
-        bf16x8 kf[2][T::KB];
+    // K fragments flow through a ring of PF+1 register slots, PF k-steps ahead of the MFMAs that use them, and
+    // the stream does not stop at tile boundaries: the last steps of a tile already pull the first fragments of
+    // the next one (it has been in the LDS ring for a whole iteration), so no MFMA waits on an LDS round trip.
+    constexpr int PF = SWEEP2 ? 1 : 3;                 // sweep 2 is short of registers (row constants, column sums)
+    bf16x8 kf[PF + 1][T::KB];
+    auto frag_load = [&](int slot, int kk, int ring) {  // keys kb*32 + l32, channels kk*16 + g2*8 .. +8
+        const unsigned char* kbase = lds + slot * T::LDS_K + l32 * T::ROW_BYTES + g2 * 16 + kk * 32;
 #pragma unroll
-        for (int kb = 0; kb < T::KB; ++kb) kf[0][kb] = frag(kb, 0);
+        for (int kb = 0; kb < T::KB; ++kb)
+            kf[ring][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * T::ROW_BYTES);
+    };
+    auto mfma_phase = [&](int slot, int slot_next) {
 #pragma unroll
         for (int kk = 0; kk < T::KK; ++kk) {
-            if (kk + 1 < T::KK) {
-#pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb) kf[(kk + 1) & 1][kb] = frag(kb, kk + 1);
-            }
+            // step kk + PF: in this tile, or the head of the next one
+            if (kk + PF < T::KK) frag_load(slot, kk + PF, (kk + PF) % (PF + 1));
+            else                 frag_load(slot_next, kk + PF - T::KK, (kk + PF) % (PF + 1));
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
@@ -234,10 +237,12 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
                     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                     const f32x16 cin = (kk == 0) ? zero : acc[rb][kb];
                     if (SWEEP2)   // C[row][key]: lane = key l32, rows c_row(i, g2)
-                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf[kk & 1][kb], cin, 0, 0, 0);
+                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf[kk % (PF + 1)][kb], cin, 0, 0, 0);
                     else          // C[key][row]: lane = row l32, keys c_row(i, g2)
-                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][kb], qf[rb][kk], cin, 0, 0, 0);
+                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % (PF + 1)][kb], qf[rb][kk], cin, 0, 0, 0);
                 }
+            // the scheduler may not move the loads of a later step down to just before their use
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     auto reduce_phase = [&](auto masked_tag, int cbuf, int j0) {
@@ -322,18 +327,23 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
         else              reduce_phase(std::false_type{}, cbuf, t * T::TK);
     };
 
+    static_assert(T::KK % (PF + 1) == 0, "the fragment ring must line up across tiles");
     const bool late = wave >= 4;                        // shares its SIMD with wave - 4
     __syncthreads();                                    // the first tiles are in the ring
+#pragma unroll
+    for (int kk = 0; kk < PF; ++kk) frag_load(0, kk, kk);
     int slot_r = 0;
     for (int t = t_begin; t <= t_end; ++t) {            // one drain iteration, like the loader wave
+        const int slot_n = (slot_r == T::STAGES - 1) ? 0 : slot_r + 1;
+        // past the last tile the fragment stream reads a stale slot: harmless, nothing consumes it
         if (late) {
             if (t > t_begin) reduce_tile(t - 1);
-            if (t < t_end) mfma_phase(slot_r);
+            if (t < t_end) mfma_phase(slot_r, slot_n);
         } else if (t < t_end) {
-            mfma_phase(slot_r);
+            mfma_phase(slot_r, slot_n);
             reduce_tile(t);
         }
-        slot_r = (slot_r == T::STAGES - 1) ? 0 : slot_r + 1;
+        slot_r = slot_n;
         __syncthreads();
     }
 
