@@ -5,6 +5,7 @@ here with torch and returned."""
 from __future__ import annotations
 
 import ctypes as C
+import dataclasses
 import os
 from dataclasses import dataclass
 from typing import Optional, Sequence, Tuple
@@ -188,15 +189,17 @@ def allocate(p: Params, weights: torch.Tensor, n_segments: int, heads_per_segmen
 
 
 def smooth(p: Params, scores: torch.Tensor, seqlens: Sequence[int], cutoff_frac: float, alpha: float, *,
-           cu_seqlens: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+           cu_seqlens: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+           workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     _need(scores, torch.float32, "scores")
     dev = scores.device
     cu = cu_seqlens if cu_seqlens is not None else _cu(seqlens, dev)
     if out is None:
         out = torch.empty_like(scores)
+    ws = _workspace(dataclasses.replace(p, window=0), seqlens, dev, workspace)
     cp = p.c()
     _check(_lib.audiokv_smooth(C.byref(cp), _ptr(scores), _ptr(cu), _host_lens(seqlens), len(seqlens),
-                               float(cutoff_frac), float(alpha), _ptr(out), None, 0, _stream()))
+                               float(cutoff_frac), float(alpha), _ptr(out), _ptr(ws), ws.numel(), _stream()))
     return out
 
 

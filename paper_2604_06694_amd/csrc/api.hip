@@ -102,10 +102,10 @@ Geom make_geom(const audiokv_params* p, int n_items) {
 }
 
 struct Workspace {
-    size_t stats_off = 0, raw_off = 0, smooth_off = 0, total = 0;
+    size_t stats_off = 0, raw_off = 0, smooth_off = 0, fft_off = 0, total = 0;
 };
 
-Workspace plan_workspace(const audiokv_params* p, const Batch& b) {
+Workspace plan_workspace(const audiokv_params* p, const Batch& b, const int32_t* seqlens_host) {
     Workspace w;
     const int n_heads = b.n_items * p->n_kv_heads;
     const int rows = (p->n_q_heads / p->n_kv_heads) * (p->window > 0 ? p->window : 1);
@@ -119,6 +119,8 @@ Workspace plan_workspace(const audiokv_params* p, const Batch& b) {
     off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
     w.smooth_off = off;
     off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
+    w.fft_off = off;          // arbitrary-length spectral smoothing (empty when every length is a power of two)
+    off += align_up(smooth_workspace_bytes(seqlens_host, b.n_items, p->n_kv_heads), 256);
     w.total = off;
     return w;
 }
@@ -146,7 +148,7 @@ int32_t check_smooth_lengths(const Batch& b, const int32_t* seqlens_host, double
     for (int i = 0; i < b.n_items; ++i)
         if (!smooth_supported(seqlens_host[i]))
             return fail(AUDIOKV_E_UNSUPPORTED, "item %d: spectral smoothing of length %d is not built "
-                        "(power-of-two lengths from 4 to 32768)", i, seqlens_host[i]);
+                        "(lengths up to 32768)", i, seqlens_host[i]);
     return AUDIOKV_OK;
 }
 
@@ -211,7 +213,7 @@ int32_t audiokv_workspace_bytes(const audiokv_params* params, int32_t n_items, c
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
     if (!out_bytes) return fail(AUDIOKV_E_INVALID_ARG, "out_bytes is NULL");
-    *out_bytes = plan_workspace(params, b).total;
+    *out_bytes = plan_workspace(params, b, seqlens_host).total;
     return AUDIOKV_OK;
 }
 
@@ -226,7 +228,7 @@ int32_t audiokv_score(const audiokv_params* params, const void* q_win, const voi
         return fail(AUDIOKV_E_INVALID_ARG, "audiokv_score: NULL pointer argument");
     if (!aligned16(q_win) || !aligned16(k)) return fail(AUDIOKV_E_INVALID_ARG, "q_win and k must be 16-byte aligned");
     AUDIOKV_TRY(check_score_shape(params));
-    const Workspace w = plan_workspace(params, b);
+    const Workspace w = plan_workspace(params, b, seqlens_host);
     if (workspace_bytes < w.total)
         return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
     const Geom g = make_geom(params, n_items);
@@ -276,7 +278,6 @@ int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, con
                        const int32_t* seqlens_host, int32_t n_items, double cutoff_frac, double alpha,
                        float* scores_out, void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     AUDIOKV_TRY(check_params(params, 0));
     audiokv_params p2 = *params;
     p2.window = 0;                                // lengths are not tied to the window here
@@ -285,9 +286,17 @@ int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, con
     if (!scores_in || !scores_out || !cu_seqlens_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_smooth: NULL pointer argument");
     AUDIOKV_TRY(check_smooth_args(cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
+    void* fft_ws = nullptr;
+    if (alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0) {
+        const Workspace w = plan_workspace(&p2, b, seqlens_host);
+        if (!workspace || workspace_bytes < w.total)
+            return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed (lengths that are not powers "
+                        "of two use a global-memory transform)", workspace ? workspace_bytes : (size_t)0, w.total);
+        fft_ws = static_cast<char*>(workspace) + w.fft_off;
+    }
     const Geom g = make_geom(params, n_items);
     AUDIOKV_HIP(launch_smooth(g, scores_in, false, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha,
-                              scores_out, static_cast<hipStream_t>(stream)),
+                              scores_out, fft_ws, static_cast<hipStream_t>(stream)),
                 "smooth kernel");
     return AUDIOKV_OK;
 }
@@ -357,7 +366,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     const int n_heads = n_items * params->n_kv_heads;
     if (alloc_scope == AUDIOKV_SCOPE_GLOBAL && n_heads > 1536)
         return fail(AUDIOKV_E_UNSUPPORTED, "global pool of %d heads > 1536", n_heads);
-    const Workspace w = plan_workspace(params, b);
+    const Workspace w = plan_workspace(params, b, seqlens_host);
     if (workspace_bytes < w.total)
         return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
 
@@ -382,7 +391,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr), "score kernels");
     AUDIOKV_MARK(2);
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
-                              alpha, smoothed, s), "smooth kernel");
+                              alpha, smoothed, ws + w.fft_off, s), "smooth kernel");
     AUDIOKV_MARK(3);
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");

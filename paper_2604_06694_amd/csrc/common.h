@@ -53,9 +53,11 @@ hipError_t launch_allocate(const Geom& g, const float* weights, int n_segments, 
 
 // pool_on_load: input holds un-pooled scores and the pooling of Geom is applied while loading.
 bool smooth_supported(int L);
+// Global-memory scratch of the arbitrary-length transform (0 when every length is a power of two).
+size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv);
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, hipStream_t s);
+                         float* out, void* workspace, hipStream_t s);
 
 bool select_supported(int L);
 hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budgets, const int32_t* cu_budgets,

@@ -8,6 +8,11 @@
 // and inverted by a decimation-in-time FFT (bit-reversed in, natural out), so
 // no reordering pass is needed. Twiddles come from two small tables filled
 // from float64 sincospi: w^e = hi[e >> 7] * lo[e & 127].
+//
+// Any other length (the transform length must be exactly L: zero-padding would be a different circular
+// filter) goes through Bluestein's chirp-z identity: a length-L DFT is a circular convolution with a chirp,
+// done with power-of-two FFTs of size M >= 2L - 1 in a per-head global-memory workspace. Stages whose span
+// exceeds the LDS (M > 16384) run on global memory, the rest on 16384-point chunks inside LDS.
 #include "common.h"
 
 namespace audiokv {
@@ -54,6 +59,8 @@ constexpr int kFftThreads = 1024;
 constexpr int kMaxPow2L = 32768;          // 128 KiB of fp32 in LDS
 constexpr int kTwLo = 128;
 
+__host__ __device__ inline bool pow2_length(int L) { return L >= 4 && L <= kMaxPow2L && (L & (L - 1)) == 0; }
+
 struct cf { float re, im; };
 __device__ __forceinline__ cf cmul(cf a, cf b) { return {a.re * b.re - a.im * b.im, a.re * b.im + a.im * b.re}; }
 __device__ __forceinline__ cf cadd(cf a, cf b) { return {a.re + b.re, a.im + b.im}; }
@@ -80,12 +87,13 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     float* dst = out + off;
     const int tid = threadIdx.x;
 
-    if (alpha == 0.f || L < 4 || (L & (L - 1)) != 0) {
-        // alpha = 0: the mix returns s itself. (Other lengths never reach this kernel.)
+    if (alpha == 0.f) {
+        // alpha = 0: the mix returns s itself, whatever the length
         for (int j = tid; j < L; j += kFftThreads)
             dst[j] = pool_on_load ? pooled_at(src, L, j, g.pool_kernel, g.pool_mode) : src[j];
         return;
     }
+    if (!pow2_length(L)) return;                      // the chirp-z kernel owns this head
 
     const int N = L >> 1;                         // complex length
     const int logN = 31 - __clz(N);
@@ -180,6 +188,166 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     }
 }
 
+// ------------------------ arbitrary length: Bluestein over global memory -----------------------
+
+constexpr int kChunkLog = 14;                     // 16384 complex = 128 KiB: the part of an FFT that fits in LDS
+constexpr int kMaxBluesteinLog = 16;              // M <= 65536, i.e. L <= 32768
+
+__host__ __device__ inline int bluestein_log(int L) {     // smallest power of two >= 2L - 1
+    int lg = 1;
+    while ((1 << lg) < 2 * L - 1) ++lg;
+    return lg;
+}
+
+// exp(-i*pi*n^2/L): the chirp, from an exactly reduced angle in float64
+__device__ __forceinline__ cf chirp(int n, int L) {
+    const long long r = ((long long)n * n) % (2LL * L);
+    double sn, cs;
+    sincospi((double)r / (double)L, &sn, &cs);
+    return {(float)cs, (float)(-sn)};
+}
+
+// exp(-2*pi*i*e/M) for 0 <= e < M/2 from the two tables of root M
+__device__ __forceinline__ cf tw_m(const cf* lo, const cf* hi, int e) { return cmul(hi[e >> 7], lo[e & (kTwLo - 1)]); }
+
+// In-place FFT of `x` (global, M = 2^logM complex). Forward: decimation in frequency, natural order in,
+// bit-reversed out. Inverse: decimation in time with conjugate twiddles, bit-reversed in, natural out,
+// unnormalised. `z` is an LDS scratch of min(M, 16384) complex; lo/hi are the twiddle tables of root M.
+__device__ void fft_pass(cf* __restrict__ x, int logM, bool inverse, cf* z, const cf* lo, const cf* hi) {
+    const int tid = threadIdx.x;
+    const int M = 1 << logM;
+    const int logC = logM < kChunkLog ? logM : kChunkLog;
+    const int C = 1 << logC;
+    auto global_stage = [&](int s) {
+        const int m = 1 << s;
+        for (int b = tid; b < (M >> 1); b += kFftThreads) {
+            const int j = b & (m - 1);
+            const int i = ((b >> s) << (s + 1)) | j;
+            const cf w = tw_m(lo, hi, j << (logM - 1 - s));
+            const cf a = x[i], c = x[i + m];
+            if (!inverse) { x[i] = cadd(a, c); x[i + m] = cmul(csub(a, c), w); }
+            else { const cf cw = cmul(c, cconj(w)); x[i] = cadd(a, cw); x[i + m] = csub(a, cw); }
+        }
+        __syncthreads();
+    };
+    auto chunk_stages = [&]() {
+        for (int base = 0; base < M; base += C) {
+            for (int i = tid; i < C; i += kFftThreads) z[i] = x[base + i];
+            __syncthreads();
+            for (int q = 0; q < logC; ++q) {
+                const int s = inverse ? q : logC - 1 - q;
+                const int m = 1 << s;
+                for (int b = tid; b < (C >> 1); b += kFftThreads) {
+                    const int j = b & (m - 1);
+                    const int i = ((b >> s) << (s + 1)) | j;
+                    const cf w = tw_m(lo, hi, j << (logM - 1 - s));
+                    const cf a = z[i], c = z[i + m];
+                    if (!inverse) { z[i] = cadd(a, c); z[i + m] = cmul(csub(a, c), w); }
+                    else { const cf cw = cmul(c, cconj(w)); z[i] = cadd(a, cw); z[i + m] = csub(a, cw); }
+                }
+                __syncthreads();
+            }
+            for (int i = tid; i < C; i += kFftThreads) x[base + i] = z[i];
+            __syncthreads();
+        }
+    };
+    if (!inverse) {
+        for (int s = logM - 1; s >= logC; --s) global_stage(s);
+        chunk_stages();
+    } else {
+        chunk_stages();
+        for (int s = logC; s < logM; ++s) global_stage(s);
+    }
+}
+
+__global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
+    Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
+    double cutoff_frac, float alpha, float* __restrict__ out, cf* __restrict__ ws, size_t ws_stride)
+{
+    extern __shared__ float smem[];
+    const int head = blockIdx.x;
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    const int tok0 = cu_seq[item];
+    const int L = cu_seq[item + 1] - tok0;
+    if (alpha == 0.f || pow2_length(L)) return;       // the LDS kernel owns this head
+    const size_t off = (size_t)tok0 * g.H_kv + (size_t)h * L;
+    const float* src = in + off;
+    float* dst = out + off;
+    const int tid = threadIdx.x;
+    const int logM = bluestein_log(L);
+    const int M = 1 << logM;
+    const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
+    cf* z = reinterpret_cast<cf*>(smem);
+    cf* lo = z + C;
+    cf* hi = lo + kTwLo;
+    const int n_hi = (M >> 8) + 1;                    // exponents below M/2
+    cf* A = ws + (size_t)head * ws_stride;
+    cf* B = A + M;
+
+    for (int t = tid; t < kTwLo + n_hi; t += kFftThreads) {
+        const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
+        double sn, cs;
+        sincospi(2.0 * (double)e / (double)M, &sn, &cs);
+        const cf w = {(float)cs, (float)(-sn)};
+        if (t < kTwLo) lo[t] = w; else hi[t - kTwLo] = w;
+    }
+    // the convolution kernel conj(chirp), wrapped around M, and the chirped input
+    for (int n = tid; n < M; n += kFftThreads) {
+        cf b = {0.f, 0.f}, a = {0.f, 0.f};
+        if (n < L) {
+            const cf w = chirp(n, L);
+            b = cconj(w);
+            const float sv = pool_on_load ? pooled_at(src, L, n, g.pool_kernel, g.pool_mode) : src[n];
+            a = {sv * w.re, sv * w.im};
+        } else if (n > M - L) {
+            b = cconj(chirp(M - n, L));
+        }
+        B[n] = b;
+        A[n] = a;
+    }
+    __syncthreads();
+    fft_pass(B, logM, false, z, lo, hi);
+    fft_pass(A, logM, false, z, lo, hi);
+    for (int n = tid; n < M; n += kFftThreads) A[n] = cmul(A[n], B[n]);
+    __syncthreads();
+    fft_pass(A, logM, true, z, lo, hi);
+
+    // F_k = chirp(k) * A[k] / M; low-pass mask on the two-sided bin index (Eq. 17-18); the inverse transform is
+    // the conjugate of a forward transform of conj(F~), so feed conj(F~) * chirp into the same machinery
+    const int kstar = (int)floor(cutoff_frac * (double)(L >> 1));
+    const float inv_m = 1.0f / (float)M;
+    for (int k = tid; k < M; k += kFftThreads) {
+        cf v = {0.f, 0.f};
+        if (k < L) {
+            const int bin = k < L - k ? k : L - k;
+            if (bin <= kstar) {
+                const cf w = chirp(k, L);
+                cf F = cmul(w, A[k]);
+                F = {F.re * inv_m, F.im * inv_m};
+                v = cmul(cconj(F), w);
+            }
+        }
+        A[k] = v;
+    }
+    __syncthreads();
+    fft_pass(A, logM, false, z, lo, hi);
+    for (int n = tid; n < M; n += kFftThreads) A[n] = cmul(A[n], B[n]);
+    __syncthreads();
+    fft_pass(A, logM, true, z, lo, hi);
+
+    // s~_n = Re(chirp(n) * A[n]) / (M * L); residual mix (Eq. 20)
+    const float scale = inv_m / (float)L;
+    for (int n = tid; n < L; n += kFftThreads) {
+        const cf y = cmul(chirp(n, L), A[n]);
+        const float st = y.re * scale;
+        if (alpha == 1.f) dst[n] = st;
+        else {
+            const float s0 = pool_on_load ? pooled_at(src, L, n, g.pool_kernel, g.pool_mode) : src[n];
+            dst[n] = (1.f - alpha) * s0 + alpha * st;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
@@ -191,25 +359,52 @@ hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlen
     return hipGetLastError();
 }
 
-bool smooth_supported(int L) { return L >= 4 && L <= kMaxPow2L && (L & (L - 1)) == 0; }
+bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && bluestein_log(L) <= kMaxBluesteinLog); }
+
+size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
+    int max_log = 0;
+    for (int i = 0; i < n_items; ++i)
+        if (!pow2_length(seqlens_host[i])) max_log = max(max_log, bluestein_log(seqlens_host[i]));
+    if (max_log == 0) return 0;
+    return (size_t)n_items * H_kv * 2 * ((size_t)1 << max_log) * sizeof(cf);
+}
 
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, hipStream_t s)
+                         float* out, void* workspace, hipStream_t s)
 {
-    int max_L = 0;
-    for (int i = 0; i < n_items; ++i) max_L = max(max_L, seqlens_host[i]);
-    const int n_hi = (max_L >> 8) + 1;
-    const size_t smem = (size_t)max_L * sizeof(float) + (size_t)(kTwLo + n_hi) * sizeof(cf);
+    int max_pow2 = 0, max_log = 0;
+    for (int i = 0; i < n_items; ++i) {
+        if (pow2_length(seqlens_host[i])) max_pow2 = max(max_pow2, seqlens_host[i]);
+        else max_log = max(max_log, bluestein_log(seqlens_host[i]));
+    }
+    const int n_heads = g.n_items * g.H_kv;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_pow2_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_bluestein_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(smooth_pow2_kernel, dim3(g.n_items * g.H_kv), dim3(kFftThreads), smem, s, g, in,
-                       pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out);
+    // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
+    if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
+        const int n_hi = (max_pow2 >> 8) + 1;
+        const size_t smem = (size_t)max_pow2 * sizeof(float) + (size_t)(kTwLo + n_hi) * sizeof(cf);
+        hipLaunchKernelGGL(smooth_pow2_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
+                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out);
+    }
+    if (max_log > 0 && alpha != 0.0) {
+        if (!workspace) return hipErrorInvalidValue;
+        const size_t M = (size_t)1 << max_log;
+        const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
+        const size_t smem = (C + kTwLo + (M >> 8) + 1) * sizeof(cf);
+        hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
+                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out,
+                           static_cast<cf*>(workspace), 2 * M);
+    }
     return hipGetLastError();
 }
 

@@ -159,6 +159,16 @@ def test_config4_concentrated_weights(A):
     assert b.max() == cfg.seqlen             # at least one head keeps everything
 
 
+def test_config5_ragged_batch(A):
+    cfg = get_config(5)                      # 8 sequences, lengths log-uniform in [2048, 32768], d = 256, per-sequence budgets
+    run_and_check(A, cfg, sample_heads=[0, 1, 6, 7, 10, 15])
+
+
+def test_ragged_small_mixed_lengths(A):
+    cfg = get_config(5, n_items=5, window=8, ratio=0.5)
+    run_and_check(A, cfg, sample_heads=range(10), lens=[100, 1024, 333, 2048, 47])
+
+
 def test_small_odd_shapes(A):
     # ragged tail tiles, tiny L, window = L - small
     for L, W, ratio in [(64, 8, 0.5), (128, 32, 0.4), (512, 64, 0.3), (1024, 32, 0.9)]:

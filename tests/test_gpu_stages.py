@@ -206,6 +206,39 @@ def test_smooth_L32768_and_in_place(A):
     assert rel_err(out[1], ref) <= SCORE_RTOL
 
 
+@pytest.mark.parametrize("L", [5, 33, 100, 1000, 2049, 5003, 12345, 20000, 32767])
+def test_smooth_arbitrary_length(A, L):
+    # transform length is exactly L (no zero padding): chirp-z path
+    rng = np.random.default_rng(L)
+    H_kv = 2
+    p = A.Params(H_kv, H_kv, 128, 1)
+    s = (np.abs(rng.standard_normal((H_kv, L))) + 0.05 * rng.standard_normal((H_kv, L))).astype(np.float32)
+    for c, alpha in [(0.125, 1.0), (0.3, 0.5)]:
+        out = A.smooth(p, torch.from_numpy(s.reshape(-1)).cuda(), [L], c, alpha)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy().reshape(H_kv, L)
+        for h in range(H_kv):
+            ref = O.smooth(s[h].astype(np.float64), c, alpha)
+            assert rel_err(out[h], ref) <= SCORE_RTOL
+            assert np.abs(out[h] - ref).max() <= 1e-4 * np.abs(ref).max()
+
+
+def test_smooth_mixed_lengths_in_one_call(A):
+    rng = np.random.default_rng(12)
+    lens = [1024, 777, 4096, 3001]
+    H_kv = 2
+    p = A.Params(H_kv, H_kv, 128, 1)
+    parts = [np.abs(rng.standard_normal((H_kv, L))).astype(np.float32) for L in lens]
+    flat = np.concatenate([x.reshape(-1) for x in parts])
+    out = A.smooth(p, torch.from_numpy(flat).cuda(), lens, 0.125, 1.0).cpu().numpy()
+    off = 0
+    for x, L in zip(parts, lens):
+        for h in range(H_kv):
+            ref = O.smooth(x[h].astype(np.float64), 0.125, 1.0)
+            assert rel_err(out[off:off + L], ref) <= SCORE_RTOL
+            off += L
+
+
 # -------------------------------------------------------------------- score
 
 def _score_case(A, H_q, H_kv, W, d, lens, *, causal=1, layout=0, pool_kernel=7, pool_mode=0, k_scale=1.0, seed=0):
