@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--cutoff", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
+                         "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -56,6 +59,20 @@ def algorithmic_bytes(cfg, lens, ratio):
         per["indices_rw"] += 2 * 4 * nk * H
     per["total"] = sum(per.values())
     return per
+
+
+def measured_traffic(workload: str) -> dict:
+    """HBM bytes per launch measured with rocprofv3 --pmc for this workload's default settings, as recorded
+    (already scaled by the copy-kernel calibration) in profiles/<workload>_hbm_traffic.md; {} if absent."""
+    short = {"cfg3_long_audio_L32768": "evict_cfg3_L32768_hbm_traffic.md"}.get(workload)
+    path = os.path.join(ROOT, "profiles", short) if short else None
+    out = {}
+    if path and os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == "traffic" and parts[2] == "=":
+                out[parts[1]] = float(parts[3])
+    return out
 
 
 def cpu_baseline(cfg, item0, w, L, ratio, cutoff, alpha):
@@ -122,6 +139,13 @@ def main():
         A.evict(p, q, k, v, w, lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=scope, cu_seqlens=cu,
                 workspace=ws, outputs=outs)
 
+    if args.pmc_calibration:
+        cal_src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).fill_(1)
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -161,6 +185,8 @@ def main():
         roof = {"bound": "hbm", "achieved": ab[key] / dom_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    if args.ratio is None and args.cutoff is None:
+        roof["traffic"] = measured_traffic(cfg.name).get(dominant)
 
     res = {
         "metric": "prefill KV tokens evicted/sec per layer (1 GPU) + achieved HBM GB/s fraction",
