@@ -171,7 +171,7 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
             slot_w = (slot_w == T::STAGES - 1) ? 0 : slot_w + 1;
             // unconditional (past the end it re-reads the last tile into a slot nobody reads again)
             AUDIOKV_FETCH(min(t + 3, t_end - 1))
-            // column sums of tile t - 2 are complete: half of the waves wrote them one iteration late
+            // column sums of tile t - 2 are complete and visible (written in iteration t - 2, barriers since)
             if (SWEEP2 && t - 2 >= t_begin) flush_cols((t - 2 - t_begin) % 3, (t - 2) * T::TK);
             __syncthreads();
         }
@@ -206,146 +206,182 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) { run_m[rb] = -INFINITY; run_l[rb] = 0.f; }
 
-    // One tile = an MFMA phase (all logits of this wave's rows x the tile's keys) and a reduction phase (the
-    // sweep's exp2 / sums on those logits). The matrix pipe and the vector ALU of a SIMD are shared by the two
-    // waves that live on it, and a barrier per tile keeps them in step, so both would run their MFMA phases
-    // together and then their reductions together. Waves 4.. therefore run their reduction one tile late
-    // (reduce(t-1), then mfma(t)): on every SIMD one wave is in the matrix pipe while the other is in the ALU.
-    // K fragments are pulled from LDS one k-step ahead of the MFMAs that use them (two register slots).
-    f32x16 acc[NB][T::KB];
-    // K fragments flow through a ring of PF+1 register slots, PF k-steps ahead of the MFMAs that use them, and
-    // the stream does not stop at tile boundaries: the last steps of a tile already pull the first fragments of
-    // the next one (it has been in the LDS ring for a whole iteration), so no MFMA waits on an LDS round trip.
-    constexpr int PF = SWEEP2 ? 1 : 3;                 // sweep 2 is short of registers (row constants, column sums)
-    bf16x8 kf[PF + 1][T::KB];
-    auto frag_load = [&](int slot, int kk, int ring) {  // keys kb*32 + l32, channels kk*16 + g2*8 .. +8
-        const unsigned char* kbase = lds + slot * T::LDS_K + l32 * T::ROW_BYTES + g2 * 16 + kk * 32;
-#pragma unroll
-        for (int kb = 0; kb < T::KB; ++kb)
-            kf[ring][kb] = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * T::ROW_BYTES);
+    // The unit of work is a block: this wave's NB*32 rows x 32 keys (NB MFMA result tiles, KK MFMAs each). Its
+    // logits then need the sweep's vector work (fma, exp2, add per logit), which costs about as much ALU time as
+    // the MFMAs cost matrix-pipe time. The two are software-pipelined inside the wave: while the MFMAs of block
+    // b + 1 accumulate into one register set, the reduction of block b runs on the other, interleaved k-step by
+    // k-step (one MFMA per row tile, then one eighth of the reduction), so the ALU work sits in the shadow of the
+    // matrix pipe. K fragments come from LDS through a small register ring, PF k-steps ahead, and the stream
+    // runs on into the next block, whose tile is already in the LDS ring.
+    constexpr int PF = 2;                               // fragment prefetch distance (k-steps)
+    constexpr int RING = 4;
+    static_assert(T::KK % RING == 0 && PF < RING, "the fragment ring must line up across blocks");
+    constexpr int SLICE = 16 / (T::KK < 16 ? T::KK : 16);   // result elements reduced per k-step (per row tile)
+    static_assert(T::KK <= 16 ? (SLICE * T::KK == 16) : true, "reduction slices must cover the 16 elements");
+    f32x16 acc0[NB], acc1[NB];
+    bf16x8 kfr[RING];
+    auto frag_load = [&](int slot, int kb, int kk, int ring) {   // keys kb*32 + l32, channels kk*16 + g2*8 .. +8
+        kfr[ring] = *reinterpret_cast<const bf16x8*>(lds + slot * T::LDS_K + (kb * 32 + l32) * T::ROW_BYTES +
+                                                     g2 * 16 + kk * 32);
     };
-    auto mfma_phase = [&](int slot, int slot_next) {
-#pragma unroll
-        for (int kk = 0; kk < T::KK; ++kk) {
-            // step kk + PF: in this tile, or the head of the next one
-            if (kk + PF < T::KK) frag_load(slot, kk + PF, (kk + PF) % (PF + 1));
-            else                 frag_load(slot_next, kk + PF - T::KK, (kk + PF) % (PF + 1));
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb)
-#pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb) {
-                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    const f32x16 cin = (kk == 0) ? zero : acc[rb][kb];
-                    if (SWEEP2)   // C[row][key]: lane = key l32, rows c_row(i, g2)
-                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kf[kk % (PF + 1)][kb], cin, 0, 0, 0);
-                    else          // C[key][row]: lane = row l32, keys c_row(i, g2)
-                        acc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % (PF + 1)][kb], qf[rb][kk], cin, 0, 0, 0);
-                }
-            // the scheduler may not move the loads of a later step down to just before their use
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    auto reduce_phase = [&](auto masked_tag, int cbuf, int j0) {
+
+    // --- reduction of one block, cut into KK slices -------------------------------------------------------------
+    float red_c[NB];                                    // sweep 1: base-2 reference of the block in flight
+    float red_s[2];                                     // partial sums (two chains)
+    f32x4 red_rc[NB];                                   // sweep 2: row constants of the 4 rows being reduced
+    auto reduce_begin = [&](auto masked_tag, f32x16 (&a)[NB], int j0b) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        float colsum[T::KB][2];
+        red_s[0] = red_s[1] = 0.f;
+        if (!SWEEP2) {
 #pragma unroll
-        for (int kb = 0; kb < T::KB; ++kb) colsum[kb][0] = colsum[kb][1] = 0.f;
-        // The row constants are re-read from LDS in every tile. Passing their offset through an empty asm keeps
-        // the compiler from proving the reads tile-invariant and hoisting all of them (32 registers) out of the loop.
-        int rc_off = row0 + g2 * 4;
-        asm volatile("" : "+v"(rc_off));
-#pragma unroll
-        for (int rb = 0; rb < NB; ++rb) {
-            if (!SWEEP2) {
+            for (int rb = 0; rb < NB; ++rb) {
                 if (MASKED) {
                     const int lv = last_visible(g, L, R, row0 + rb * 32 + l32);
 #pragma unroll
-                    for (int kb = 0; kb < T::KB; ++kb)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            if (j0 + kb * 32 + c_row(i, g2) > lv) acc[rb][kb][i] = -INFINITY;
+                    for (int i = 0; i < 16; ++i)
+                        if (j0b + c_row(i, g2) > lv) a[rb][i] = -INFINITY;
                 }
-                float mx = -INFINITY;
+                float mx = a[rb][0];
 #pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][kb][i]);
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
                 const float m_new = fmaxf(run_m[rb], mx);
                 const float ms = (m_new == -INFINITY) ? 0.f : m_new;
-                const float msc = ms * c;
-                float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < T::KB; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; i += 2) {
-                        s0 += fast_exp2(fmaf(acc[rb][kb][i], c, -msc));
-                        s1 += fast_exp2(fmaf(acc[rb][kb][i + 1], c, -msc));
-                    }
-                run_l[rb] = run_l[rb] * fast_exp2((run_m[rb] - ms) * c) + (s0 + s1);
+                red_c[rb] = ms * c;
+                run_l[rb] *= fast_exp2((run_m[rb] - ms) * c);
                 run_m[rb] = m_new;
-            } else {
-                if (MASKED) {
+            }
+        } else if (MASKED) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int lv = last_visible(g, L, R, row0 + rb * 32 + c_row(i, g2));
+            for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
-                        for (int kb = 0; kb < T::KB; ++kb)
-                            if (j0 + kb * 32 + l32 > lv) acc[rb][kb][i] = -INFINITY;
-                    }
-                }
+                for (int i = 0; i < 16; ++i)
+                    if (j0b + l32 > last_visible(g, L, R, row0 + rb * 32 + c_row(i, g2))) a[rb][i] = -INFINITY;
+        }
+    };
+    auto reduce_slice = [&](f32x16 (&a)[NB], int sl) {  // elements [sl*SLICE, (sl+1)*SLICE) of every row tile
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {           // rows 8*q4 + 4*g2 + {0..3}: one 16-byte read
-                    const f32x4 rc = *reinterpret_cast<const f32x4*>(lds_rc + rc_off + rb * 32 + q4 * 8);
+        for (int rb = 0; rb < NB; ++rb) {
 #pragma unroll
-                    for (int kb = 0; kb < T::KB; ++kb) {
-                        colsum[kb][0] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 0], c, -rc[0]));
-                        colsum[kb][1] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 1], c, -rc[1]));
-                        colsum[kb][0] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 2], c, -rc[2]));
-                        colsum[kb][1] += fast_exp2(fmaf(acc[rb][kb][q4 * 4 + 3], c, -rc[3]));
-                    }
+            for (int e = 0; e < SLICE; ++e) {
+                const int i = sl * SLICE + e;
+                if (SWEEP2) {
+                    // rows 8*(i/4) + 4*g2 + {0..3}: one 16-byte read serves four elements
+                    if ((i & 3) == 0)                   // slices of a block run in order, so the constants persist
+                        red_rc[rb] = *reinterpret_cast<const f32x4*>(lds_rc + row0 + g2 * 4 + rb * 32 + (i >> 2) * 8);
+                    red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_rc[rb][i & 3]));
+                } else {
+                    if (rb == 0) red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
+                    else         run_l[rb] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
                 }
             }
         }
+    };
+    auto reduce_end = [&](int cbuf, int kb) {
         if (SWEEP2) {
             // rows held by the other half of the wave; the other waves' rows are added by the loader wave
-#pragma unroll
-            for (int kb = 0; kb < T::KB; ++kb) {
-                float v = colsum[kb][0] + colsum[kb][1];
-                v += __shfl_xor(v, 32, 64);
-                if (g2 == 0) lds_cols[cbuf * (WR * T::TK) + wave * T::TK + kb * 32 + l32] = v;
-            }
+            float v = red_s[0] + red_s[1];
+            v += __shfl_xor(v, 32, 64);
+            if (g2 == 0) lds_cols[cbuf * (WR * T::TK) + wave * T::TK + kb * 32 + l32] = v;
+        } else {
+            run_l[0] += red_s[0] + red_s[1];
         }
-    };
-    // does any (row, key) pair of tile t need the visibility test?
-    auto is_masked = [&](int t) {
-        const int j0 = t * T::TK;
-        return g.causal ? (j0 + T::TK - 1 > L - g.W) : (j0 + T::TK > L);
-    };
-    auto reduce_tile = [&](int t) {
-        const int cbuf = (t - t_begin) % 3;
-        if (is_masked(t)) reduce_phase(std::true_type{}, cbuf, t * T::TK);
-        else              reduce_phase(std::false_type{}, cbuf, t * T::TK);
     };
 
-    static_assert(T::KK % (PF + 1) == 0, "the fragment ring must line up across tiles");
-    const bool late = wave >= 4;                        // shares its SIMD with wave - 4
-    __syncthreads();                                    // the first tiles are in the ring
+    // --- one pipelined step sequence: MFMAs of block (slot_m, kb_m) into `am`, reduction of `ar` ---------------
+    // stream = true: fragments of the first PF k-steps are already in the ring, and the last PF steps pull the
+    // head of the next block (slot_n, kb_n). stream = false: the block loads its own fragments.
+    auto run_block = [&](auto do_mfma_tag, auto do_red_tag, auto stream_tag, f32x16 (&am)[NB], int slot_m, int kb_m,
+                         int slot_n, int kb_n, f32x16 (&ar)[NB]) {
+        constexpr bool DO_MFMA = decltype(do_mfma_tag)::value;
+        constexpr bool DO_RED = decltype(do_red_tag)::value;
+        constexpr bool STREAM = decltype(stream_tag)::value;
+        if (DO_MFMA && !STREAM) {
 #pragma unroll
-    for (int kk = 0; kk < PF; ++kk) frag_load(0, kk, kk);
-    int slot_r = 0;
-    for (int t = t_begin; t <= t_end; ++t) {            // one drain iteration, like the loader wave
-        const int slot_n = (slot_r == T::STAGES - 1) ? 0 : slot_r + 1;
-        // past the last tile the fragment stream reads a stale slot: harmless, nothing consumes it
-        if (late) {
-            if (t > t_begin) reduce_tile(t - 1);
-            if (t < t_end) mfma_phase(slot_r, slot_n);
-        } else if (t < t_end) {
-            mfma_phase(slot_r, slot_n);
-            reduce_tile(t);
+            for (int kk = 0; kk < PF; ++kk) frag_load(slot_m, kb_m, kk, kk % RING);
         }
-        slot_r = slot_n;
+#pragma unroll
+        for (int kk = 0; kk < T::KK; ++kk) {
+            if (DO_MFMA) {
+                if (kk + PF < T::KK) frag_load(slot_m, kb_m, kk + PF, (kk + PF) % RING);
+                else if (STREAM)     frag_load(slot_n, kb_n, kk + PF - T::KK, (kk + PF) % RING);
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    const f32x16 cin = (kk == 0) ? zero : am[rb];
+                    if (SWEEP2)   // C[row][key]: lane = key l32, rows c_row(i, g2)
+                        am[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][kk], kfr[kk % RING], cin, 0, 0, 0);
+                    else          // C[key][row]: lane = row l32, keys c_row(i, g2)
+                        am[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk % RING], qf[rb][kk], cin, 0, 0, 0);
+                }
+            }
+            if (DO_RED && kk < 16) reduce_slice(ar, kk);
+            // keep each k-step together: one MFMA per row tile with its slice of vector work behind it
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using Y = std::true_type;
+    using N = std::false_type;
+
+    // Tiles from t_plain_end on contain (row, key) pairs that need the visibility test: always the tail of a head.
+    const int t_first_masked = g.causal ? (L - g.W + 1) / T::TK : L / T::TK;
+    const int t_plain_end = min(max(t_first_masked, t_begin), t_end);
+    auto slot_of = [&](int t) { return (t - t_begin) % T::STAGES; };
+
+    __syncthreads();                                    // the first tiles are in the ring
+    int t = t_begin;
+    if (t < t_plain_end) {
+        // ---- pipelined part: blocks (t, 0), (t, 1), (t + 1, 0), ... ; acc0 holds even blocks, acc1 odd ones
+        run_block(Y{}, N{}, N{}, acc0, slot_of(t), 0, 0, 0, acc1);           // prologue: MFMAs of the first block
+        // its last steps did not prefetch: start the stream for the second block
+        if (T::KB == 2) {
+#pragma unroll
+            for (int kk = 0; kk < PF; ++kk) frag_load(slot_of(t), 1, kk, kk % RING);
+            for (; t < t_plain_end; ++t) {
+                const bool more = t + 1 < t_plain_end;
+                const int cbuf = (t - t_begin) % 3;
+                reduce_begin(N{}, acc0, t * T::TK);
+                run_block(Y{}, Y{}, Y{}, acc1, slot_of(t), 1, slot_of(t + 1), 0, acc0);
+                reduce_end(cbuf, 0);
+                reduce_begin(N{}, acc1, t * T::TK + 32);
+                if (more) run_block(Y{}, Y{}, Y{}, acc0, slot_of(t + 1), 0, slot_of(t + 1), 1, acc1);
+                else      run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
+                reduce_end(cbuf, 1);
+                __syncthreads();
+            }
+        } else {
+            // one block per tile: two tiles per trip so that the accumulator sets alternate statically. The MFMAs
+            // run one tile ahead (tile t + 1 is visible since the last barrier); the fragment stream must not run
+            // on into tile t + 2, which the loader is depositing right now, so every block loads its own.
+            while (t < t_plain_end) {
+                reduce_begin(N{}, acc0, t * T::TK);
+                if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc1, slot_of(t + 1), 0, 0, 0, acc0);
+                else                     run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
+                reduce_end((t - t_begin) % 3, 0);
+                ++t;
+                __syncthreads();
+                if (t >= t_plain_end) break;
+                reduce_begin(N{}, acc1, t * T::TK);
+                if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc0, slot_of(t + 1), 0, 0, 0, acc1);
+                else                     run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
+                reduce_end((t - t_begin) % 3, 0);
+                ++t;
+                __syncthreads();
+            }
+        }
+    }
+    // ---- masked tail (at most a few tiles per head): plain sequence, with the visibility test
+    for (; t < t_end; ++t) {
+        const int cbuf = (t - t_begin) % 3;
+#pragma unroll
+        for (int kb = 0; kb < T::KB; ++kb) {
+            run_block(Y{}, N{}, N{}, acc0, slot_of(t), kb, 0, 0, acc1);
+            reduce_begin(Y{}, acc0, t * T::TK + kb * 32);
+            run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
+            reduce_end(cbuf, kb);
+        }
         __syncthreads();
     }
+    __syncthreads();                                    // the drain iteration of the loader wave
 
     if (!SWEEP2) {
         // a row's keys are spread over the two halves of the wave
