@@ -228,10 +228,17 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     // --- reduction of one block, cut into KK slices -------------------------------------------------------------
     float red_c[NB];                                    // sweep 1: base-2 reference of the block in flight
     float red_s[2];                                     // partial sums (two chains)
-    f32x4 red_rc[NB];                                   // sweep 2: row constants of the 4 rows being reduced
+    f32x4 red_rc[2][NB];                                // sweep 2: row constants of 4 rows, loaded one group ahead
+    // rows 8*q4 + 4*g2 + {0..3} of every row tile: one 16-byte LDS read serves four result elements
+    auto rc_load = [&](int q4) {
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+            red_rc[q4 & 1][rb] = *reinterpret_cast<const f32x4*>(lds_rc + row0 + g2 * 4 + rb * 32 + q4 * 8);
+    };
     auto reduce_begin = [&](auto masked_tag, f32x16 (&a)[NB], int j0b) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         red_s[0] = red_s[1] = 0.f;
+        if (SWEEP2) rc_load(0);
         if (!SWEEP2) {
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
@@ -260,15 +267,15 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     };
     auto reduce_slice = [&](f32x16 (&a)[NB], int sl) {  // elements [sl*SLICE, (sl+1)*SLICE) of every row tile
 #pragma unroll
-        for (int rb = 0; rb < NB; ++rb) {
+        for (int e = 0; e < SLICE; ++e) {
+            const int i = sl * SLICE + e;
+            // the constants of the next four elements are requested a group ahead of their use, so that the
+            // wait for them never drains the K fragments that were prefetched behind them
+            if (SWEEP2 && (i & 3) == 0 && i + 4 < 16) rc_load((i >> 2) + 1);
 #pragma unroll
-            for (int e = 0; e < SLICE; ++e) {
-                const int i = sl * SLICE + e;
+            for (int rb = 0; rb < NB; ++rb) {
                 if (SWEEP2) {
-                    // rows 8*(i/4) + 4*g2 + {0..3}: one 16-byte read serves four elements
-                    if ((i & 3) == 0)                   // slices of a block run in order, so the constants persist
-                        red_rc[rb] = *reinterpret_cast<const f32x4*>(lds_rc + row0 + g2 * 4 + rb * 32 + (i >> 2) * 8);
-                    red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_rc[rb][i & 3]));
+                    red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_rc[(i >> 2) & 1][rb][i & 3]));
                 } else {
                     if (rb == 0) red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
                     else         run_l[rb] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
