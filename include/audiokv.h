@@ -17,8 +17,9 @@
  *   failure on the calling thread (library-owned, valid until the next call).
  * - "device" pointers are HIP device memory owned by the caller; "host"
  *   pointers are ordinary host memory. The library allocates no device memory
- *   and keeps no state between calls: scratch comes from the caller's
- *   `workspace` (size from audiokv_workspace_bytes).
+ *   and keeps no data between calls: scratch comes from the caller's
+ *   `workspace` (size from audiokv_workspace_bytes). (audiokv_evict owns one
+ *   helper stream and two events, see there.)
  * - Calls validate their arguments on the host, enqueue kernels on `stream`
  *   (a hipStream_t passed as void*; NULL = the default stream) and return
  *   without synchronising. Inputs, outputs and workspace must stay alive, and
@@ -189,7 +190,12 @@ int32_t audiokv_compact(const audiokv_params* params,
  * n_items * n_kv_heads heads, all L_i equal). weights_dev: fp32
  * [n_items * n_kv_heads], one per KV head. Intermediate scores live in the
  * workspace. Outputs as in the per-stage calls; the result equals the five
- * calls composed. */
+ * calls composed. The budget allocation does not depend on the scores, so it is
+ * forked onto a helper stream owned by the library (created on first use,
+ * default priority) and joined back into `stream` with events before the
+ * selection; everything is ordered after prior work on `stream` and before
+ * later work on it. Because that helper stream and its two events are shared,
+ * audiokv_evict must not be called from several host threads at once. */
 int32_t audiokv_evict(const audiokv_params* params,
                       const void* q_win, const void* k, const void* v,
                       const float* weights_dev, int32_t alloc_scope,

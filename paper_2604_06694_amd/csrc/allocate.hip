@@ -79,16 +79,30 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
     // proportional shares with the cap: heads over the cap are fixed at it and
     // the rest of the budget is shared again among the others
     for (;;) {
-        if (tid == 0) {
+        if (tid < 64) {
+            // In-order float64 sum of the free heads' weights. The order is fixed (head 0, 1, 2, ...), so the adds
+            // are serial, but the operands are staged 64 at a time in the lanes of one wave and read back with
+            // readlane, instead of one LDS round trip per head from a single thread.
             int ncap = 0, nfree = 0;
             double tot = 0.0;
-            for (int h = 0; h < n; ++h) {
-                if (flag[h] & 1) ++ncap;
-                else { tot = __dadd_rn(tot, S[h]); ++nfree; }
+            for (int base = 0; base < n; base += 64) {
+                const int h = base + tid;
+                const double sv = h < n ? S[h] : 0.0;
+                const int fv = h < n ? flag[h] : 0;
+                const int cnt = min(64, n - base);
+                for (int j = 0; j < cnt; ++j) {
+                    const int lo = __builtin_amdgcn_readlane(__double2loint(sv), j);
+                    const int hi = __builtin_amdgcn_readlane(__double2hiint(sv), j);
+                    const int fj = __builtin_amdgcn_readlane(fv, j);
+                    if (fj & 1) ++ncap;
+                    else { tot = __dadd_rn(tot, __hiloint2double(hi, lo)); ++nfree; }
+                }
             }
-            sh->tot = tot;
-            sh->n_free = nfree;
-            sh->T = (double)(Bs - (long long)ncap * cap);
+            if (tid == 0) {
+                sh->tot = tot;
+                sh->n_free = nfree;
+                sh->T = (double)(Bs - (long long)ncap * cap);
+            }
         }
         __syncthreads();
         const double tot = sh->tot, T = sh->T;
@@ -172,11 +186,18 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
     for (int h = h0; h < h1; ++h) chunk += f + e[h];
     red[tid] = chunk;
     __syncthreads();
-    if (tid == 0) {                               // 256-entry serial exclusive scan
-        long long run = 0;
-        for (int t = 0; t < kThreads; ++t) { const long long c = red[t]; red[t] = run; run += c; }
-        if (seg == n_segments - 1) cu_budgets[(size_t)n_segments * n] = (int32_t)(base + run);
+    // exclusive scan of the 256 chunk totals (integers: any order), total to the last segment's end marker
+    const long long mine = chunk;
+    for (int off = 1; off < kThreads; off <<= 1) {
+        const long long add = tid >= off ? red[tid - off] : 0;
+        __syncthreads();
+        red[tid] += add;
+        __syncthreads();
     }
+    if (tid == kThreads - 1 && seg == n_segments - 1) cu_budgets[(size_t)n_segments * n] = (int32_t)(base + red[tid]);
+    const long long excl = red[tid] - mine;
+    __syncthreads();
+    red[tid] = excl;
     __syncthreads();
     long long run = base + red[tid];
     for (int h = h0; h < h1; ++h) {

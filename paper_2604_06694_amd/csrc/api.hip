@@ -168,6 +168,21 @@ struct Profile {
     hipEvent_t ev[AUDIOKV_PROFILE_STAGES + 2] = {};    // last slot: between the two score sweeps
 } g_prof;
 
+// audiokv_evict forks the (tiny, score-independent) allocation onto a helper stream so that it runs under the
+// score kernels instead of in front of them. Created on first use, kept for the life of the process.
+struct Helper {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+} g_helper;
+
+hipError_t ensure_helper() {
+    if (g_helper.stream) return hipSuccess;
+    hipError_t e = hipStreamCreateWithFlags(&g_helper.stream, hipStreamNonBlocking);   // default priority
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&g_helper.fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&g_helper.join, hipEventDisableTiming);
+    return e;
+}
+
 #define AUDIOKV_TRY(expr)                  \
     do {                                   \
         const int32_t rc__ = (expr);       \
@@ -384,8 +399,18 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     const bool prof = g_prof.enabled && g_prof.created;
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
     AUDIOKV_MARK(0);
-    AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
-                                budgets_dev, cu_budgets_dev, s), "allocate kernel");
+    if (prof) {
+        // stage timing wants one kernel per interval: keep the allocation in line
+        AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
+                                    budgets_dev, cu_budgets_dev, s), "allocate kernel");
+    } else {
+        AUDIOKV_HIP(ensure_helper(), "helper stream");
+        AUDIOKV_HIP(hipEventRecord(g_helper.fork, s), "hipEventRecord");
+        AUDIOKV_HIP(hipStreamWaitEvent(g_helper.stream, g_helper.fork, 0), "hipStreamWaitEvent");
+        AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
+                                    budgets_dev, cu_budgets_dev, g_helper.stream), "allocate kernel");
+        AUDIOKV_HIP(hipEventRecord(g_helper.join, g_helper.stream), "hipEventRecord");
+    }
     AUDIOKV_MARK(1);
     AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr), "score kernels");
@@ -393,6 +418,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, ws + w.fft_off, s), "smooth kernel");
     AUDIOKV_MARK(3);
+    if (!prof) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
     AUDIOKV_MARK(4);
