@@ -21,7 +21,7 @@ bool make_plan(int rows, int D, Plan* out) {
     for (int i = 0; i < n; ++i) {                     // sorted by padded rows: the first that fits pads least
         const int pad = cs[i].NB * 32 * cs[i].WR;
         if (pad >= rows) {
-            *out = Plan{cs[i].NB, cs[i].WR, pad, (D == 256) ? 32 : 64};
+            *out = Plan{cs[i].NB, cs[i].WR, pad, (D == 256) ? 32 : 32 * AUDIOKV_SCORE_KB};
             return true;
         }
     }

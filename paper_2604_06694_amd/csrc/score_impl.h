@@ -43,6 +43,10 @@
 
 #include "common.h"
 
+#ifndef AUDIOKV_SCORE_KB
+#define AUDIOKV_SCORE_KB 2
+#endif
+
 namespace audiokv {
 namespace score_detail {
 
@@ -53,7 +57,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 template <int D, int NB, int WR>
 struct Tile {
     static constexpr int THREADS = 64 * (WR + 1);      // WR compute waves + 1 loader wave
-    static constexpr int KB = (D == 256) ? 1 : 2;     // 32-key blocks per tile
+    static constexpr int KB = (D == 256) ? 1 : AUDIOKV_SCORE_KB;   // 32-key blocks per tile
     static constexpr int TK = 32 * KB;                // keys per tile
     static constexpr int KK = D / 16;                 // MFMA k-steps per logit
     static constexpr int ROWS = NB * 32 * WR;         // padded window rows per head
@@ -127,11 +131,15 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
 
     // sweep 2: add the WR waves' partial column sums of the tile starting at j0 (fixed order) and store them
     auto flush_cols = [&](int buf, int j0) {
-        if (lane < T::TK && j0 + lane < L) {
-            float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < WR; ++w) v += lds_cols[buf * (WR * T::TK) + w * T::TK + lane];
-            raw[(size_t)tok0 * g.H_kv + (size_t)h * L + j0 + lane] = v;
+        for (int cc = 0; cc < T::TK; cc += 64) {
+            const int col = cc + lane;
+            if (col < T::TK && j0 + col < L) {
+                float v = 0.f;
+#pragma unroll
+                for (int w = 0; w < WR; ++w) v += lds_cols[buf * (WR * T::TK) + w * T::TK + col];
+                raw[(size_t)tok0 * g.H_kv + (size_t)h * L + j0 + col] = v;
+            }
         }
     };
 
@@ -340,19 +348,30 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
         // ---- pipelined part: blocks (t, 0), (t, 1), (t + 1, 0), ... ; acc0 holds even blocks, acc1 odd ones
         run_block(Y{}, N{}, N{}, acc0, slot_of(t), 0, 0, 0, acc1);           // prologue: MFMAs of the first block
         // its last steps did not prefetch: start the stream for the second block
-        if (T::KB == 2) {
+        if (T::KB >= 2) {
+            static_assert(T::KB == 1 || T::KB % 2 == 0, "the accumulator sets alternate by block parity");
 #pragma unroll
             for (int kk = 0; kk < PF; ++kk) frag_load(slot_of(t), 1, kk, kk % RING);
             for (; t < t_plain_end; ++t) {
                 const bool more = t + 1 < t_plain_end;
                 const int cbuf = (t - t_begin) % 3;
-                reduce_begin(N{}, acc0, t * T::TK);
-                run_block(Y{}, Y{}, Y{}, acc1, slot_of(t), 1, slot_of(t + 1), 0, acc0);
-                reduce_end(cbuf, 0);
-                reduce_begin(N{}, acc1, t * T::TK + 32);
-                if (more) run_block(Y{}, Y{}, Y{}, acc0, slot_of(t + 1), 0, slot_of(t + 1), 1, acc1);
-                else      run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
-                reduce_end(cbuf, 1);
+#pragma unroll
+                for (int kb = 0; kb < T::KB; ++kb) {
+                    // block in flight on the matrix pipe: (t, kb + 1), or the first block of the next tile; the
+                    // fragment stream then runs on into the block after that one
+                    const bool wrap1 = kb + 1 >= T::KB, wrap2 = kb + 2 >= T::KB;
+                    const int slot_m = wrap1 ? slot_of(t + 1) : slot_of(t), kb_m = wrap1 ? kb + 1 - T::KB : kb + 1;
+                    const int slot_n = wrap2 ? slot_of(t + 1) : slot_of(t), kb_n = wrap2 ? kb + 2 - T::KB : kb + 2;
+                    if ((kb & 1) == 0) {
+                        reduce_begin(N{}, acc0, t * T::TK + kb * 32);
+                        run_block(Y{}, Y{}, Y{}, acc1, slot_m, kb_m, slot_n, kb_n, acc0);
+                    } else {
+                        reduce_begin(N{}, acc1, t * T::TK + kb * 32);
+                        if (!wrap1 || more) run_block(Y{}, Y{}, Y{}, acc0, slot_m, kb_m, slot_n, kb_n, acc1);
+                        else                run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
+                    }
+                    reduce_end(cbuf, kb);
+                }
                 __syncthreads();
             }
         } else {

@@ -3,11 +3,15 @@
 //
 // SSS for a power-of-two L runs entirely inside one workgroup's LDS: the real
 // sequence is viewed as L/2 complex numbers, transformed by an in-place
-// radix-2 decimation-in-frequency FFT (natural order in, bit-reversed out),
+// decimation-in-frequency FFT (natural order in, bit-reversed out),
 // turned into the real spectrum pair by pair, masked above k*, turned back,
 // and inverted by a decimation-in-time FFT (bit-reversed in, natural out), so
-// no reordering pass is needed. Twiddles come from two small tables filled
-// from float64 sincospi: w^e = hi[e >> 7] * lo[e & 127].
+// no reordering pass is needed. Four radix-2 stages at a time run in registers
+// (16 points per thread), so the data crosses LDS, and the workgroup meets at
+// a barrier, once per four stages. Twiddles come from two small tables filled
+// from float64 sincospi: w^e = hi[e >> 7] * lo[e & 127]; the part of a twiddle
+// that depends on the position inside the 16-point group is a constant 16th
+// root of unity.
 //
 // Any other length (the transform length must be exactly L: zero-padding would be a different circular
 // filter) goes through Bluestein's chirp-z identity: a length-L DFT is a circular convolution with a chirp,
@@ -72,6 +76,113 @@ __device__ __forceinline__ cf twiddle(const cf* lo, const cf* hi, int e) {
     return cmul(hi[e >> 7], lo[e & (kTwLo - 1)]);
 }
 
+// LDS slot of complex element i. One spare slot per 16 elements: a thread's 16-point group at stride 1 or 4 would
+// otherwise sit in a single bank.
+__device__ __forceinline__ int pad(int i) { return i + (i >> 4); }
+__host__ __device__ constexpr size_t padded_len(size_t n) { return n + (n >> 4) + 1; }
+
+// w * exp(-2*pi*i*k/16) for k = 0..7; k is a compile-time constant once the callers' loops are unrolled
+__device__ __forceinline__ cf mul_root16(cf w, int k) {
+    constexpr float C1 = 0.92387953251128674f, S1 = 0.38268343236508977f, H = 0.70710678118654752f;
+    switch (k) {
+        case 0:  return w;
+        case 1:  return cmul(w, {C1, -S1});
+        case 2:  return cmul(w, {H, -H});
+        case 3:  return cmul(w, {S1, -C1});
+        case 4:  return {w.im, -w.re};
+        case 5:  return cmul(w, {-S1, -C1});
+        case 6:  return cmul(w, {-H, -H});
+        default: return cmul(w, {-C1, -S1});
+    }
+}
+
+// R decimation-in-frequency stages (half-sizes 2^s down to 2^(s-R+1)) of an in-place FFT on n complex points in
+// LDS. The twiddle of stage s' at offset j inside its half is root^(j << (tw_shift - s')), root = exp(-2*pi*i/2^(tw_shift+1)).
+// A thread owns the 2^R points that differ in index bits [s-R+1, s]. Ends with a barrier.
+template <int R>
+__device__ __forceinline__ void dif_pass(cf* z, int n, int s, int tw_shift, const cf* lo, const cf* hi) {
+    const int sb = s - R + 1;
+    for (int gi = threadIdx.x; gi < (n >> R); gi += kFftThreads) {
+        const int j0 = gi & ((1 << sb) - 1);
+        const int base = ((gi >> sb) << (sb + R)) | j0;
+        cf v[1 << R];
+#pragma unroll
+        for (int q = 0; q < (1 << R); ++q) v[q] = z[pad(base + (q << sb))];
+        const int e0 = j0 << (tw_shift - s);
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const int bit = R - 1 - t;
+            const cf wt = twiddle(lo, hi, e0 << t);      // the part of the exponent that comes from j0
+#pragma unroll
+            for (int q = 0; q < (1 << R); ++q) {
+                if (q & (1 << bit)) continue;
+                const int qlow = q & ((1 << bit) - 1);   // the part that comes from the position in the group
+                const cf tw = mul_root16(wt, (qlow << t) << (4 - R));
+                const cf a = v[q], c = v[q | (1 << bit)];
+                v[q] = cadd(a, c);
+                v[q | (1 << bit)] = cmul(csub(a, c), tw);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < (1 << R); ++q) z[pad(base + (q << sb))] = v[q];
+    }
+    __syncthreads();
+}
+
+// R decimation-in-time stages (half-sizes 2^s0 up to 2^(s0+R-1)) with conjugate twiddles: the mirror image.
+template <int R>
+__device__ __forceinline__ void dit_pass(cf* z, int n, int s0, int tw_shift, const cf* lo, const cf* hi) {
+    for (int gi = threadIdx.x; gi < (n >> R); gi += kFftThreads) {
+        const int j0 = gi & ((1 << s0) - 1);
+        const int base = ((gi >> s0) << (s0 + R)) | j0;
+        cf v[1 << R];
+#pragma unroll
+        for (int q = 0; q < (1 << R); ++q) v[q] = z[pad(base + (q << s0))];
+        const int e0 = j0 << (tw_shift - s0 - R + 1);
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            const cf wt = twiddle(lo, hi, e0 << (R - 1 - t));
+#pragma unroll
+            for (int q = 0; q < (1 << R); ++q) {
+                if (q & (1 << t)) continue;
+                const int qlow = q & ((1 << t) - 1);
+                const cf tw = cconj(mul_root16(wt, qlow << (3 - t)));
+                const cf a = v[q], c = cmul(v[q | (1 << t)], tw);
+                v[q] = cadd(a, c);
+                v[q | (1 << t)] = csub(a, c);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < (1 << R); ++q) z[pad(base + (q << s0))] = v[q];
+    }
+    __syncthreads();
+}
+
+// all log2(n) stages on LDS-resident data: forward = natural order in, bit-reversed out; inverse = the reverse,
+// unnormalised
+__device__ __forceinline__ void fft_lds(cf* z, int logn, int tw_shift, bool inverse, const cf* lo, const cf* hi) {
+    const int n = 1 << logn;
+    if (!inverse) {
+        for (int s = logn - 1; s >= 0;) {
+            const int R = s + 1 < 4 ? s + 1 : 4;
+            if (R == 4) dif_pass<4>(z, n, s, tw_shift, lo, hi);
+            else if (R == 3) dif_pass<3>(z, n, s, tw_shift, lo, hi);
+            else if (R == 2) dif_pass<2>(z, n, s, tw_shift, lo, hi);
+            else dif_pass<1>(z, n, s, tw_shift, lo, hi);
+            s -= R;
+        }
+    } else {
+        for (int s0 = 0; s0 < logn;) {
+            const int R = logn - s0 < 4 ? logn - s0 : 4;
+            if (R == 4) dit_pass<4>(z, n, s0, tw_shift, lo, hi);
+            else if (R == 3) dit_pass<3>(z, n, s0, tw_shift, lo, hi);
+            else if (R == 2) dit_pass<2>(z, n, s0, tw_shift, lo, hi);
+            else dit_pass<1>(z, n, s0, tw_shift, lo, hi);
+            s0 += R;
+        }
+    }
+}
+
 __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
     double cutoff_frac, float alpha,
@@ -97,14 +208,22 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
 
     const int N = L >> 1;                         // complex length
     const int logN = 31 - __clz(N);
-    float* x = smem;                              // L floats = N complex
-    cf* z = reinterpret_cast<cf*>(smem);
-    cf* lo = reinterpret_cast<cf*>(smem + L);     // kTwLo entries: w^j
+    cf* z = reinterpret_cast<cf*>(smem);          // N complex = L floats, padded
+    cf* lo = z + padded_len(N);                   // kTwLo entries: w^j
     cf* hi = lo + kTwLo;                          // (L/2)/128 + 1 entries: w^(128 j)
     const int n_hi = (N >> 7) + 1;
 
-    for (int j = tid; j < L; j += kFftThreads)
-        x[j] = pool_on_load ? pooled_at(src, L, j, g.pool_kernel, g.pool_mode) : src[j];
+    for (int i = tid; i < N; i += kFftThreads) {
+        cf v;
+        if (pool_on_load) {
+            v.re = pooled_at(src, L, 2 * i, g.pool_kernel, g.pool_mode);
+            v.im = pooled_at(src, L, 2 * i + 1, g.pool_kernel, g.pool_mode);
+        } else {
+            v.re = src[2 * i];
+            v.im = src[2 * i + 1];
+        }
+        z[pad(i)] = v;
+    }
     for (int t = tid; t < kTwLo + n_hi; t += kFftThreads) {
         const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
         double sn, cs;
@@ -114,19 +233,8 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     }
     __syncthreads();
 
-    // forward: decimation in frequency, half-size m = N/2 ... 1
-    for (int s = logN - 1; s >= 0; --s) {
-        const int m = 1 << s;
-        for (int b = tid; b < (N >> 1); b += kFftThreads) {
-            const int j = b & (m - 1);
-            const int i = ((b >> s) << (s + 1)) | j;
-            const cf a = z[i], c = z[i + m];
-            z[i] = cadd(a, c);
-            // w_N^(j * N/(2m)) = w_L^(2 * j * N/(2m)) = w_L^(j << (logN - s))
-            z[i + m] = cmul(csub(a, c), twiddle(lo, hi, j << (logN - s)));
-        }
-        __syncthreads();
-    }
+    // forward transform of the half-length complex sequence; stage twiddles w_N^(j N/(2m)) = w_L^(j << (logN - s))
+    fft_lds(z, logN, logN, false, lo, hi);
 
     // spectrum of the real sequence, low-pass mask (Eq. 17-18), and back, pair (k, N-k) at a time
     const int kstar = (int)floor(cutoff_frac * (double)N);     // N = floor(L/2) = n_bins - 1
@@ -139,8 +247,13 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
             z[0] = {0.5f * (X0 + XN), 0.5f * (X0 - XN)};
             continue;
         }
-        const int pa = logN ? (int)(__brev((unsigned)k) >> shift) : 0;
-        const int pb = logN ? (int)(__brev((unsigned)(N - k)) >> shift) : 0;
+        const int pa = pad(logN ? (int)(__brev((unsigned)k) >> shift) : 0);
+        const int pb = pad(logN ? (int)(__brev((unsigned)(N - k)) >> shift) : 0);
+        if (k > kstar && N - k > kstar) {                       // both bins masked
+            z[pa] = {0.f, 0.f};
+            z[pb] = {0.f, 0.f};
+            continue;
+        }
         const cf A = z[pa];
         const cf B = cconj(z[pb]);
         const cf E = {0.5f * (A.re + B.re), 0.5f * (A.im + B.im)};
@@ -162,29 +275,21 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     }
     __syncthreads();
 
-    // inverse: decimation in time, half-size m = 1 ... N/2, conjugate twiddles
-    for (int s = 0; s < logN; ++s) {
-        const int m = 1 << s;
-        for (int b = tid; b < (N >> 1); b += kFftThreads) {
-            const int j = b & (m - 1);
-            const int i = ((b >> s) << (s + 1)) | j;
-            const cf a = z[i];
-            const cf c = cmul(z[i + m], cconj(twiddle(lo, hi, j << (logN - s))));
-            z[i] = cadd(a, c);
-            z[i + m] = csub(a, c);
-        }
-        __syncthreads();
-    }
+    fft_lds(z, logN, logN, true, lo, hi);
 
     // residual mix (Eq. 20); 1/N completes the inverse transform
     const float inv = 1.0f / (float)N;
-    for (int j = tid; j < L; j += kFftThreads) {
-        const float st = x[j] * inv;
-        if (alpha == 1.f) dst[j] = st;
-        else {
-            const float s0 = pool_on_load ? pooled_at(src, L, j, g.pool_kernel, g.pool_mode) : src[j];
-            dst[j] = (1.f - alpha) * s0 + alpha * st;
+    for (int i = tid; i < N; i += kFftThreads) {
+        const cf st = z[pad(i)];
+        float o0 = st.re * inv, o1 = st.im * inv;
+        if (alpha != 1.f) {
+            const float a0 = pool_on_load ? pooled_at(src, L, 2 * i, g.pool_kernel, g.pool_mode) : src[2 * i];
+            const float a1 = pool_on_load ? pooled_at(src, L, 2 * i + 1, g.pool_kernel, g.pool_mode) : src[2 * i + 1];
+            o0 = (1.f - alpha) * a0 + alpha * o0;
+            o1 = (1.f - alpha) * a1 + alpha * o1;
         }
+        dst[2 * i] = o0;
+        dst[2 * i + 1] = o1;
     }
 }
 
@@ -212,8 +317,8 @@ __device__ __forceinline__ cf tw_m(const cf* lo, const cf* hi, int e) { return c
 
 // In-place FFT of `x` (global, M = 2^logM complex). Forward: decimation in frequency, natural order in,
 // bit-reversed out. Inverse: decimation in time with conjugate twiddles, bit-reversed in, natural out,
-// unnormalised. `z` is an LDS scratch of min(M, 16384) complex; lo/hi are the twiddle tables of root M.
-__device__ void fft_pass(cf* __restrict__ x, int logM, bool inverse, cf* z, const cf* lo, const cf* hi) {
+// unnormalised. `z` is a padded LDS scratch for min(M, 16384) complex; lo/hi are the twiddle tables of root M.
+__device__ __noinline__ void fft_pass(cf* __restrict__ x, int logM, bool inverse, cf* z, const cf* lo, const cf* hi) {
     const int tid = threadIdx.x;
     const int M = 1 << logM;
     const int logC = logM < kChunkLog ? logM : kChunkLog;
@@ -232,22 +337,12 @@ __device__ void fft_pass(cf* __restrict__ x, int logM, bool inverse, cf* z, cons
     };
     auto chunk_stages = [&]() {
         for (int base = 0; base < M; base += C) {
-            for (int i = tid; i < C; i += kFftThreads) z[i] = x[base + i];
+            for (int i = tid; i < C; i += kFftThreads) z[pad(i)] = x[base + i];
             __syncthreads();
-            for (int q = 0; q < logC; ++q) {
-                const int s = inverse ? q : logC - 1 - q;
-                const int m = 1 << s;
-                for (int b = tid; b < (C >> 1); b += kFftThreads) {
-                    const int j = b & (m - 1);
-                    const int i = ((b >> s) << (s + 1)) | j;
-                    const cf w = tw_m(lo, hi, j << (logM - 1 - s));
-                    const cf a = z[i], c = z[i + m];
-                    if (!inverse) { z[i] = cadd(a, c); z[i + m] = cmul(csub(a, c), w); }
-                    else { const cf cw = cmul(c, cconj(w)); z[i] = cadd(a, cw); z[i + m] = csub(a, cw); }
-                }
-                __syncthreads();
-            }
-            for (int i = tid; i < C; i += kFftThreads) x[base + i] = z[i];
+            // stage s of the whole transform, restricted to a chunk, is stage s of a C-point transform with the
+            // twiddles of root M
+            fft_lds(z, logC, logM - 1, inverse, lo, hi);
+            for (int i = tid; i < C; i += kFftThreads) x[base + i] = z[pad(i)];
             __syncthreads();
         }
     };
@@ -278,7 +373,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
     cf* z = reinterpret_cast<cf*>(smem);
-    cf* lo = z + C;
+    cf* lo = z + padded_len(C);
     cf* hi = lo + kTwLo;
     const int n_hi = (M >> 8) + 1;                    // exponents below M/2
     cf* A = ws + (size_t)head * ws_stride;
@@ -392,7 +487,7 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
     // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
     if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
         const int n_hi = (max_pow2 >> 8) + 1;
-        const size_t smem = (size_t)max_pow2 * sizeof(float) + (size_t)(kTwLo + n_hi) * sizeof(cf);
+        const size_t smem = (padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf);
         hipLaunchKernelGGL(smooth_pow2_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out);
     }
@@ -400,7 +495,7 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         if (!workspace) return hipErrorInvalidValue;
         const size_t M = (size_t)1 << max_log;
         const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
-        const size_t smem = (C + kTwLo + (M >> 8) + 1) * sizeof(cf);
+        const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf);
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out,
                            static_cast<cf*>(workspace), 2 * M);
