@@ -103,8 +103,24 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     float* lds_cols = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K);
     float* lds_rc = reinterpret_cast<float*>(lds + T::STAGES * T::LDS_K + 3 * T::LDS_COLS);
 
-    const int head = blockIdx.x / nsplit;
-    const int split = blockIdx.x - head * nsplit;
+    // Workgroups go to the 8 XCDs round-robin by index, and each XCD has its own L2. All key-range splits of a head
+    // are therefore given indices with the same residue mod 8, so that the head's window queries (and the tile
+    // shared by neighbouring splits) are fetched from HBM by one L2 only.
+    int head, split;
+    {
+        const int n_heads = gridDim.x / nsplit;
+        const int full = n_heads & ~7;                  // heads that fill whole groups of 8
+        const int bid = blockIdx.x;
+        if (bid < full * nsplit) {
+            const int q = bid >> 3;
+            split = q % nsplit;
+            head = (q / nsplit) * 8 + (bid & 7);
+        } else {
+            const int r = bid - full * nsplit;
+            head = full + r / nsplit;
+            split = r - (r / nsplit) * nsplit;
+        }
+    }
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
     const int L = cu_seq[item + 1] - tok0;
