@@ -292,33 +292,61 @@ def cutoff_bin(L: int, cutoff_frac: float) -> int:
     return int(math.floor(float(cutoff_frac) * float(L // 2)))
 
 
-def energy_cutoff_bin(F: np.ndarray, rho: float) -> int:
+def energy_cutoff_bin(F: np.ndarray, rho: float, skip_dc: bool = False) -> int:
     """Adaptive cutoff (Sec. 3.3, Eqs. 14-16): smallest k* with
-    E(k*) >= rho * E(last bin), E(k) = sum_{i<=k} |F_i|^2 (one-sided, DC included)."""
+    E(k*) >= rho * E(last bin), E(k) = sum_{i<=k} |F_i|^2 over the one-sided
+    spectrum, DC included as the equations are written. `skip_dc` is the
+    variant whose sums start at bin 1 (the DC bin of a non-negative score
+    sequence otherwise holds nearly all the energy); then k* >= 1."""
     m2 = np.abs(np.asarray(F, dtype=np.complex128)) ** 2
+    if skip_dc and m2.shape[0] > 1:
+        m2 = m2.copy()
+        m2[0] = 0.0
+        E = np.cumsum(m2)
+        target = float(rho) * E[-1]
+        return max(1, int(np.argmax(E >= target)))
     E = np.cumsum(m2)
     target = float(rho) * E[-1]
     return int(np.argmax(E >= target))
 
 
+def mask_weights(k_star: int, taper_bins: int, n_bins: int) -> np.ndarray:
+    """Frequency mask of Eqs. 17-18 with the cosine transition band that the
+    text after Eq. 17 asks for: w_i = 1 for i <= k*, then `taper_bins` bins of
+    a half-cosine roll-off, w_i = (1 + cos(pi (i - k*) / (T + 1))) / 2 for
+    k* < i <= k* + T, and 0 beyond. T = 0 is the hard mask of Eq. 17. (The paper
+    gives neither width nor exact shape of the band: this form is a reading.)"""
+    i = np.arange(n_bins, dtype=np.float64)
+    w = np.where(i <= k_star, 1.0, 0.0)
+    T = int(taper_bins)
+    if T > 0:
+        band = (i > k_star) & (i <= k_star + T)
+        w = np.where(band, 0.5 * (1.0 + np.cos(np.pi * (i - k_star) / float(T + 1))), w)
+    return w
+
+
 def smooth(s: np.ndarray, cutoff_frac: float, alpha: float, *,
-           energy_rho: Optional[float] = None) -> np.ndarray:
+           energy_rho: Optional[float] = None, skip_dc: bool = False,
+           taper_bins: int = 0, k_star: Optional[int] = None) -> np.ndarray:
     """Spectral Score Smoothing of one head's sequence (Sec. 3.3, Eqs. 13-20).
 
-    F = RDFT(s); keep bins i <= k*, zero the rest (Eq. 17-18);
+    F = RDFT(s); F~ = F * w with the mask of Eqs. 17-18 (bins i <= k* kept,
+    optional cosine roll-off over the next `taper_bins` bins);
     s~ = IRDFT(F~, L) (Eq. 19); return (1 - alpha) s + alpha s~ (Eq. 20).
     k* is the fixed fraction `cutoff_frac` of the bins, or, when `energy_rho`
-    is given, the energy-based cutoff of Eqs. 15-16.
+    is given, the energy-based cutoff of Eqs. 15-16, or `k_star` when forced.
     """
     s = np.asarray(s, dtype=np.float64)
     L = s.shape[0]
-    if energy_rho is None:
+    n_bins = L // 2 + 1
+    if k_star is not None:
+        ks = int(k_star)
+    elif energy_rho is None:
         ks = cutoff_bin(L, cutoff_frac)
-        F = rdft(s, ks)
     else:
-        Ffull = rdft(s)
-        ks = energy_cutoff_bin(Ffull, energy_rho)
-        F = Ffull[:ks + 1]
+        ks = energy_cutoff_bin(rdft(s), energy_rho, skip_dc)
+    k_top = min(ks + int(taper_bins), n_bins - 1)
+    F = rdft(s, k_top) * mask_weights(ks, taper_bins, n_bins)[:k_top + 1]
     s_tilde = irdft(F, L)
     return (1.0 - float(alpha)) * s + float(alpha) * s_tilde
 

@@ -136,3 +136,77 @@ def test_energy_cutoff_known_spectrum():
     assert O.energy_cutoff_bin(F, 0.95) == 10
     out = O.smooth(s, 0.0, 1.0, energy_rho=0.6)
     np.testing.assert_allclose(out, 1.0 + 2.0 * np.cos(2 * np.pi * 3 * n / L), atol=1e-12)
+
+
+def test_energy_cutoff_is_the_loop_definition_and_dc_variant():
+    # Eqs. 14-16 written out as loops on random spectra, with and without the DC bin
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        nb = int(rng.integers(2, 40))
+        F = rng.normal(size=nb) + 1j * rng.normal(size=nb)
+        rho = float(rng.uniform(0.05, 1.0))
+        for skip in (False, True):
+            first = 1 if skip else 0
+            total = sum(abs(F[i]) ** 2 for i in range(first, nb))
+            acc, want = 0.0, None
+            for k in range(first, nb):
+                acc += abs(F[k]) ** 2
+                if acc >= rho * total:
+                    want = k
+                    break
+            assert O.energy_cutoff_bin(F, rho, skip) == want
+    # known spectrum without DC: |F_3|^2 = L^2, |F_10|^2 = L^2/4 -> cumulative 1, 1.25 (x L^2)
+    L = 64
+    n = np.arange(L)
+    s = 1.0 + 2.0 * np.cos(2 * np.pi * 3 * n / L) + 1.0 * np.cos(2 * np.pi * 10 * n / L)
+    F = O.rdft(s)
+    assert O.energy_cutoff_bin(F, 0.5, True) == 3
+    assert O.energy_cutoff_bin(F, 0.9, True) == 10
+    # monotone in rho
+    ks = [O.energy_cutoff_bin(F, r) for r in (0.1, 0.3, 0.5, 0.7, 0.9, 0.99, 1.0)]
+    assert ks == sorted(ks)
+
+
+def test_taper_mask_shape():
+    # T = 0 is the hard mask of Eq. 17
+    w0 = O.mask_weights(5, 0, 20)
+    assert np.array_equal(w0, (np.arange(20) <= 5).astype(float))
+    for ks, T, nb in [(5, 4, 20), (0, 7, 9), (10, 3, 12), (3, 1, 8)]:
+        w = O.mask_weights(ks, T, nb)
+        assert np.all(w[:ks + 1] == 1.0) and np.all(w[ks + T + 1:] == 0.0)
+        band = w[ks + 1:min(ks + T + 1, nb)]
+        assert np.all(band > 0.0) and np.all(band < 1.0) and np.all(np.diff(np.concatenate([[1.0], band, [0.0]])) < 0)
+        # half-cosine: values mirrored about the middle of the band add up to one
+        if ks + T < nb:
+            full = w[ks + 1:ks + T + 1]
+            np.testing.assert_allclose(full + full[::-1], 1.0, atol=1e-15)
+            # closed form at the middle of an odd band: exactly one half
+            if T % 2 == 1:
+                assert abs(full[T // 2] - 0.5) < 1e-15
+
+
+def test_taper_scales_single_cosines_and_keeps_invariants():
+    L, ks_frac, T = 256, 0.125, 6            # k* = 16, band 17..22
+    n = np.arange(L)
+    ks = O.cutoff_bin(L, ks_frac)
+    w = O.mask_weights(ks, T, L // 2 + 1)
+    for k in (3, 16, 17, 19, 22, 23, 60):
+        s = np.cos(2 * np.pi * k * n / L + 0.3)
+        out = O.smooth(s, ks_frac, 1.0, taper_bins=T)
+        np.testing.assert_allclose(out, w[k] * s, atol=1e-12)
+    rng = np.random.default_rng(11)
+    a, b = rng.normal(size=L), rng.normal(size=L)
+    fa, fb = O.smooth(a, ks_frac, 1.0, taper_bins=T), O.smooth(b, ks_frac, 1.0, taper_bins=T)
+    np.testing.assert_allclose(O.smooth(2 * a - 3 * b, ks_frac, 1.0, taper_bins=T), 2 * fa - 3 * fb, atol=1e-12)
+    assert abs(fa.mean() - a.mean()) < 1e-13
+    # a tapered mask removes less than the hard mask at k* and no more than the hard mask at k* + T
+    e = lambda x: float(np.sum(x * x))
+    assert e(O.smooth(a, ks_frac, 1.0)) <= e(fa) + 1e-12 <= e(O.smooth(a, 0, 1.0, k_star=ks + T)) + 2e-12
+    # against the library transform with the same weights
+    ref = np.fft.irfft(np.fft.rfft(a) * w, L)
+    np.testing.assert_allclose(fa, ref, atol=1e-12)
+    # band running past the Nyquist bin is simply cut there
+    out = O.smooth(a, 1.0, 1.0, taper_bins=5)
+    np.testing.assert_allclose(out, a, atol=1e-12)
+    # forced cutoff = the same cutoff reached by its fraction
+    np.testing.assert_array_equal(O.smooth(a, 0, 0.5, k_star=ks), O.smooth(a, ks_frac, 0.5))
