@@ -69,6 +69,10 @@ extern "C" {
 #define AUDIOKV_LAYOUT_HEAD_MAJOR  0   /* [H_kv][L][d] per item */
 #define AUDIOKV_LAYOUT_TOKEN_MAJOR 1   /* [L][H_kv][d] per item */
 
+#define AUDIOKV_CUTOFF_FRACTION     0  /* k* = floor(cutoff * floor(L/2)): a fixed fraction of the bins            */
+#define AUDIOKV_CUTOFF_ENERGY       1  /* smallest k* whose cumulative spectral energy reaches cutoff * total      */
+#define AUDIOKV_CUTOFF_ENERGY_NO_DC 2  /* the same with both sums starting at bin 1 (k* >= 1)                      */
+
 #define AUDIOKV_SCOPE_ITEM   0  /* each item's heads share that item's budget pool        */
 #define AUDIOKV_SCOPE_GLOBAL 1  /* all heads of all items share one pool (equal L required) */
 
@@ -86,6 +90,8 @@ typedef struct audiokv_params {
     int32_t  kv_layout;      /* AUDIOKV_LAYOUT_*                                       */
     float    softmax_scale;  /* 0 selects 1/sqrt(head_dim)                             */
     float    floor_frac;     /* beta in [0,1]: uniform floor r = floor(beta*(n_keep-W))*/
+    int32_t  cutoff_mode;    /* AUDIOKV_CUTOFF_*: how the `cutoff_frac` argument of smooth / evict sets k* */
+    int32_t  taper_bins;     /* T >= 0: bins of cosine roll-off after k* (0: hard mask) */
 } audiokv_params;
 
 /* Packed version: major * 10000 + minor * 100 + patch. */
@@ -148,18 +154,40 @@ int32_t audiokv_allocate(const audiokv_params* params,
                          double ratio,
                          int32_t* budgets_dev, int32_t* cu_budgets_dev, void* stream);
 
-/* Stage 3 - Spectral Score Smoothing (paper Sec. 3.3, Eqs. 13, 17-20):
- * F = RFFT(s) over exactly L_i points; bins above k* = floor(cutoff_frac *
- * floor(L_i/2)) are zeroed; s~ = IRFFT(F~, L_i); out = (1-alpha) s + alpha s~.
- * cutoff_frac in [0,1] (1 keeps every bin: identity), alpha in [0,1]
- * (0: bitwise copy). scores_out may alias scores_in. fp32 arithmetic with
- * float64-generated twiddles. */
+/* Stage 3 - Spectral Score Smoothing (paper Sec. 3.3, Eqs. 13-20):
+ * F = RFFT(s) over exactly L_i points; F~ = F * w; s~ = IRFFT(F~, L_i);
+ * out = (1-alpha) s + alpha s~. The mask w (Eqs. 17-18) keeps bins i <= k*,
+ * rolls off over the next params->taper_bins bins as
+ * w_i = (1 + cos(pi (i - k*) / (T + 1))) / 2 (the cosine transition band
+ * mentioned after Eq. 17; T = 0 is the hard mask) and is zero beyond.
+ * params->cutoff_mode chooses k*:
+ *   AUDIOKV_CUTOFF_FRACTION  k* = floor(cutoff_frac * floor(L_i/2)),
+ *                            cutoff_frac in [0,1] (1 keeps every bin: identity);
+ *   AUDIOKV_CUTOFF_ENERGY    Eqs. 14-16: the smallest k* with
+ *                            sum_{i<=k*} |F_i|^2 >= cutoff_frac * sum_i |F_i|^2
+ *                            over the one-sided spectrum, per head, cutoff_frac
+ *                            (the ratio rho of Eq. 16) in (0,1]; energies are
+ *                            fp32 squares accumulated in float64;
+ *   AUDIOKV_CUTOFF_ENERGY_NO_DC  the same with both sums starting at bin 1.
+ * alpha in [0,1] (0: bitwise copy). scores_out may alias scores_in. fp32
+ * arithmetic with float64-generated twiddles. */
 int32_t audiokv_smooth(const audiokv_params* params,
                        const float* scores_in,
                        const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
                        double cutoff_frac, double alpha,
                        float* scores_out,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The cutoff bin k* that audiokv_smooth would use for every head, without the
+ * filtering (paper Sec. 3.3, Eqs. 14-16 for the energy modes): kstar_dev is
+ * int32 [n_items * n_kv_heads] on the device. Same arguments, lengths and
+ * workspace as audiokv_smooth. */
+int32_t audiokv_smooth_cutoffs(const audiokv_params* params,
+                               const float* scores_in,
+                               const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                               double cutoff_frac,
+                               int32_t* kstar_dev,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /* Stage 4 - per-head top-k (paper Sec. 1, Solution 2: Top-K selection on the
  * importance scores). Head g keeps budgets[g] tokens: the last `window`

@@ -13,8 +13,9 @@ import importlib
 
 _BINDING_NAMES = (
     "AudioKVError", "Params", "allocate", "compact", "evict", "lib_path", "n_keep", "profile_enable",
-    "profile_read", "score", "select", "smooth", "total_kept", "version", "workspace_bytes",
+    "profile_read", "score", "select", "smooth", "smooth_cutoffs", "total_kept", "version", "workspace_bytes",
     "POOL_AVG", "POOL_MAX", "LAYOUT_HEAD_MAJOR", "LAYOUT_TOKEN_MAJOR", "SCOPE_ITEM", "SCOPE_GLOBAL",
+    "CUTOFF_FRACTION", "CUTOFF_ENERGY", "CUTOFF_ENERGY_NO_DC",
     "PROFILE_STAGES",
 )
 

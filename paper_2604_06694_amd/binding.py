@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libaudiokv.so")
 POOL_AVG, POOL_MAX = 0, 1
 LAYOUT_HEAD_MAJOR, LAYOUT_TOKEN_MAJOR = 0, 1
 SCOPE_ITEM, SCOPE_GLOBAL = 0, 1
+CUTOFF_FRACTION, CUTOFF_ENERGY, CUTOFF_ENERGY_NO_DC = 0, 1, 2
 
 
 class AudioKVError(RuntimeError):
@@ -39,6 +40,8 @@ class _CParams(C.Structure):
         ("kv_layout", C.c_int32),
         ("softmax_scale", C.c_float),
         ("floor_frac", C.c_float),
+        ("cutoff_mode", C.c_int32),
+        ("taper_bins", C.c_int32),
     ]
 
 
@@ -54,11 +57,13 @@ class Params:
     kv_layout: int = LAYOUT_HEAD_MAJOR
     softmax_scale: float = 0.0
     floor_frac: float = 0.1
+    cutoff_mode: int = CUTOFF_FRACTION
+    taper_bins: int = 0
 
     def c(self) -> _CParams:
         return _CParams(C.sizeof(_CParams), self.n_q_heads, self.n_kv_heads, self.head_dim, self.window,
                         self.pool_kernel, self.pool_mode, self.causal, self.kv_layout,
-                        self.softmax_scale, self.floor_frac)
+                        self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins)
 
 
 def lib_path() -> str:
@@ -81,6 +86,7 @@ def _load() -> C.CDLL:
     lib.audiokv_score.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.audiokv_allocate.argtypes = [pp, vp, i32, i32, i32, vp, vp, f64, vp, vp, vp]
     lib.audiokv_smooth.argtypes = [pp, vp, vp, vp, i32, f64, f64, vp, vp, C.c_size_t, vp]
+    lib.audiokv_smooth_cutoffs.argtypes = [pp, vp, vp, vp, i32, f64, vp, vp, C.c_size_t, vp]
     lib.audiokv_select.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.audiokv_compact.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.audiokv_evict.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
@@ -89,7 +95,7 @@ def _load() -> C.CDLL:
     lib.audiokv_profile_enable.restype = i32
     lib.audiokv_profile_read.argtypes = [C.POINTER(C.c_float)]
     lib.audiokv_profile_read.restype = i32
-    for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "select", "compact", "evict"):
+    for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "smooth_cutoffs", "select", "compact", "evict"):
         getattr(lib, "audiokv_" + name).restype = i32
     return lib
 
@@ -200,6 +206,20 @@ def smooth(p: Params, scores: torch.Tensor, seqlens: Sequence[int], cutoff_frac:
     cp = p.c()
     _check(_lib.audiokv_smooth(C.byref(cp), _ptr(scores), _ptr(cu), _host_lens(seqlens), len(seqlens),
                                float(cutoff_frac), float(alpha), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def smooth_cutoffs(p: Params, scores: torch.Tensor, seqlens: Sequence[int], cutoff_frac: float, *,
+                   cu_seqlens: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The cutoff bin k* of every head (int32 [n_items * n_kv_heads])."""
+    _need(scores, torch.float32, "scores")
+    dev = scores.device
+    cu = cu_seqlens if cu_seqlens is not None else _cu(seqlens, dev)
+    out = torch.empty(len(seqlens) * p.n_kv_heads, dtype=torch.int32, device=dev)
+    ws = _workspace(dataclasses.replace(p, window=0), seqlens, dev, workspace)
+    cp = p.c()
+    _check(_lib.audiokv_smooth_cutoffs(C.byref(cp), _ptr(scores), _ptr(cu), _host_lens(seqlens), len(seqlens),
+                                       float(cutoff_frac), _ptr(out), _ptr(ws), ws.numel(), _stream()))
     return out
 
 

@@ -50,6 +50,9 @@ int32_t check_params(const audiokv_params* p, int window_min) {
         return fail(AUDIOKV_E_INVALID_ARG, "pool_kernel %d must be odd, in [1, 1025]", p->pool_kernel);
     if (p->pool_mode != AUDIOKV_POOL_AVG && p->pool_mode != AUDIOKV_POOL_MAX)
         return fail(AUDIOKV_E_INVALID_ARG, "pool_mode %d", p->pool_mode);
+    if (p->cutoff_mode < AUDIOKV_CUTOFF_FRACTION || p->cutoff_mode > AUDIOKV_CUTOFF_ENERGY_NO_DC)
+        return fail(AUDIOKV_E_INVALID_ARG, "cutoff_mode %d", p->cutoff_mode);
+    if (p->taper_bins < 0) return fail(AUDIOKV_E_INVALID_ARG, "taper_bins %d must be >= 0", p->taper_bins);
     if (p->kv_layout != AUDIOKV_LAYOUT_HEAD_MAJOR && p->kv_layout != AUDIOKV_LAYOUT_TOKEN_MAJOR)
         return fail(AUDIOKV_E_INVALID_ARG, "kv_layout %d", p->kv_layout);
     if (p->causal != 0 && p->causal != 1) return fail(AUDIOKV_E_INVALID_ARG, "causal %d", p->causal);
@@ -98,6 +101,8 @@ Geom make_geom(const audiokv_params* p, int n_items) {
     g.layout = p->kv_layout;
     const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)p->head_dim);
     g.c_log2 = scale * 1.44269504088896340736f;
+    g.cutoff_mode = p->cutoff_mode;
+    g.taper_bins = p->taper_bins;
     return g;
 }
 
@@ -137,8 +142,10 @@ int32_t check_ratio(const audiokv_params* p, const Batch& b, const int32_t* seql
     return AUDIOKV_OK;
 }
 
-int32_t check_smooth_args(double cutoff_frac, double alpha) {
+int32_t check_smooth_args(const audiokv_params* p, double cutoff_frac, double alpha) {
     if (!(cutoff_frac >= 0.0 && cutoff_frac <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "cutoff_frac %g must lie in [0, 1]", cutoff_frac);
+    if (p->cutoff_mode != AUDIOKV_CUTOFF_FRACTION && !(cutoff_frac > 0.0))
+        return fail(AUDIOKV_E_INVALID_ARG, "energy ratio %g must lie in (0, 1]", cutoff_frac);
     if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(AUDIOKV_E_INVALID_ARG, "alpha %g must lie in [0, 1]", alpha);
     return AUDIOKV_OK;
 }
@@ -289,17 +296,20 @@ int32_t audiokv_allocate(const audiokv_params* params, const float* weights_dev,
     return AUDIOKV_OK;
 }
 
-int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, const int32_t* cu_seqlens_dev,
-                       const int32_t* seqlens_host, int32_t n_items, double cutoff_frac, double alpha,
-                       float* scores_out, void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+int32_t smooth_entry(const audiokv_params* params, const float* scores_in, const int32_t* cu_seqlens_dev,
+                     const int32_t* seqlens_host, int32_t n_items, double cutoff_frac, double alpha,
+                     float* scores_out, int32_t* kstar_dev, bool cutoffs_only, void* workspace,
+                     size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 0));
     audiokv_params p2 = *params;
     p2.window = 0;                                // lengths are not tied to the window here
     Batch b;
     AUDIOKV_TRY(check_batch(&p2, n_items, seqlens_host, &b));
-    if (!scores_in || !scores_out || !cu_seqlens_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_smooth: NULL pointer argument");
-    AUDIOKV_TRY(check_smooth_args(cutoff_frac, alpha));
+    if (!scores_in || !cu_seqlens_dev || (cutoffs_only ? !kstar_dev : !scores_out))
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_smooth: NULL pointer argument");
+    AUDIOKV_TRY(check_smooth_args(params, cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
     void* fft_ws = nullptr;
     if (alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0) {
@@ -311,9 +321,27 @@ int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, con
     }
     const Geom g = make_geom(params, n_items);
     AUDIOKV_HIP(launch_smooth(g, scores_in, false, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha,
-                              scores_out, fft_ws, static_cast<hipStream_t>(stream)),
+                              scores_out, fft_ws, kstar_dev, cutoffs_only, static_cast<hipStream_t>(stream)),
                 "smooth kernel");
     return AUDIOKV_OK;
+}
+}  // namespace
+
+int32_t audiokv_smooth(const audiokv_params* params, const float* scores_in, const int32_t* cu_seqlens_dev,
+                       const int32_t* seqlens_host, int32_t n_items, double cutoff_frac, double alpha,
+                       float* scores_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return smooth_entry(params, scores_in, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha, scores_out,
+                        nullptr, false, workspace, workspace_bytes, stream);
+}
+
+int32_t audiokv_smooth_cutoffs(const audiokv_params* params, const float* scores_in, const int32_t* cu_seqlens_dev,
+                               const int32_t* seqlens_host, int32_t n_items, double cutoff_frac,
+                               int32_t* kstar_dev, void* workspace, size_t workspace_bytes, void* stream)
+{
+    // alpha = 1: the transform has to run for the energy modes
+    return smooth_entry(params, scores_in, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, 1.0, nullptr,
+                        kstar_dev, true, workspace, workspace_bytes, stream);
 }
 
 int32_t audiokv_select(const audiokv_params* params, const float* scores, const int32_t* budgets_dev,
@@ -374,7 +402,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     if (alloc_scope == AUDIOKV_SCOPE_GLOBAL && !b.uniform)
         return fail(AUDIOKV_E_INVALID_ARG, "a global budget pool needs equal lengths (got %d..%d)", b.min_L, b.max_L);
     AUDIOKV_TRY(check_ratio(params, b, seqlens_host, ratio));
-    AUDIOKV_TRY(check_smooth_args(cutoff_frac, alpha));
+    AUDIOKV_TRY(check_smooth_args(params, cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
     AUDIOKV_TRY(check_score_shape(params));
     if (!select_supported(b.max_L)) return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d exceeds 32768", b.max_L);
@@ -416,7 +444,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr), "score kernels");
     AUDIOKV_MARK(2);
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
-                              alpha, smoothed, ws + w.fft_off, s), "smooth kernel");
+                              alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");
     AUDIOKV_MARK(3);
     if (!prof) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),

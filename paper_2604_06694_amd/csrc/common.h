@@ -22,6 +22,8 @@ struct Geom {
     int causal;
     int layout;     // AUDIOKV_LAYOUT_*
     float c_log2;   // softmax scale * log2(e): logits are handled in base-2 units
+    int cutoff_mode;   // AUDIOKV_CUTOFF_*
+    int taper_bins;    // cosine roll-off bins after k*
 };
 
 // Where head (item, h), token j starts inside the packed K/V buffers (in elements).
@@ -55,9 +57,10 @@ hipError_t launch_allocate(const Geom& g, const float* weights, int n_segments, 
 bool smooth_supported(int L);
 // Global-memory scratch of the arbitrary-length transform (0 when every length is a power of two).
 size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv);
+// kstar_out (may be null): the cutoff bin of every head; cutoffs_only stops after writing it.
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, void* workspace, hipStream_t s);
+                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s);
 
 bool select_supported(int L);
 hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budgets, const int32_t* cu_budgets,

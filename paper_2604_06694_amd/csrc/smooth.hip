@@ -183,10 +183,60 @@ __device__ __forceinline__ void fft_lds(cf* z, int logn, int tw_shift, bool inve
     }
 }
 
+// Frequency mask (Eqs. 17-18): 1 up to k*, a half-cosine roll-off over the next T bins, 0 beyond.
+__device__ __forceinline__ float mask_weight(int k, int kstar, int T) {
+    if (k <= kstar) return 1.f;
+    if (k > kstar + T) return 0.f;
+    return 0.5f * (1.f + cospif((float)(k - kstar) / (float)(T + 1)));
+}
+
+// LDS scratch of the energy search: kFftThreads partial sums and the result
+struct EnergyScratch {
+    double part[kFftThreads];
+    int cross;
+    int kstar;
+};
+
+// Adaptive cutoff (Eqs. 14-16): the smallest k >= first with sum_{first<=i<=k} e(i) >= rho * sum_{first<=i<n_bins} e(i).
+// Bin energies are fp32, all sums float64: every thread adds a contiguous run of bins, the runs' totals are
+// scanned, and the thread whose run crosses the target walks it again. Uniform result; ends synchronised.
+template <class EnergyFn>
+__device__ __forceinline__ int energy_cutoff(EnergyFn&& energy, int n_bins, int first, double rho, EnergyScratch* sc) {
+    const int tid = threadIdx.x;
+    const int per = (n_bins + kFftThreads - 1) / kFftThreads;
+    const int k0 = max(min(tid * per, n_bins), first), k1 = max(min(tid * per + per, n_bins), k0);
+    double mine = 0.0;
+    for (int k = k0; k < k1; ++k) mine += (double)energy(k);
+    sc->part[tid] = mine;
+    if (tid == 0) { sc->cross = kFftThreads; sc->kstar = min(first, n_bins - 1); }
+    __syncthreads();
+    for (int off = 1; off < kFftThreads; off <<= 1) {          // inclusive scan
+        const double add = tid >= off ? sc->part[tid - off] : 0.0;
+        __syncthreads();
+        sc->part[tid] += add;
+        __syncthreads();
+    }
+    const double target = rho * sc->part[kFftThreads - 1];
+    const double incl = sc->part[tid];
+    if (target > 0.0 && k1 > k0 && incl >= target) atomicMin(&sc->cross, tid);
+    __syncthreads();
+    if (tid == sc->cross) {
+        double acc = incl - mine;
+        int ks = k1 - 1;                                       // rounding between the two summation orders
+        for (int k = k0; k < k1; ++k) {
+            acc += (double)energy(k);
+            if (acc >= target) { ks = k; break; }
+        }
+        sc->kstar = ks;
+    }
+    __syncthreads();
+    return sc->kstar;
+}
+
 __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
     double cutoff_frac, float alpha,
-    float* __restrict__ out)
+    float* __restrict__ out, int32_t* __restrict__ kstar_out, int cutoffs_only)
 {
     extern __shared__ float smem[];
     const int head = blockIdx.x;
@@ -205,6 +255,11 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
         return;
     }
     if (!pow2_length(L)) return;                      // the chirp-z kernel owns this head
+    const int T = g.taper_bins;
+    if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && cutoffs_only) {
+        if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
+        return;
+    }
 
     const int N = L >> 1;                         // complex length
     const int logN = 31 - __clz(N);
@@ -236,20 +291,44 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     // forward transform of the half-length complex sequence; stage twiddles w_N^(j N/(2m)) = w_L^(j << (logN - s))
     fft_lds(z, logN, logN, false, lo, hi);
 
-    // spectrum of the real sequence, low-pass mask (Eq. 17-18), and back, pair (k, N-k) at a time
-    const int kstar = (int)floor(cutoff_frac * (double)N);     // N = floor(L/2) = n_bins - 1
     const int shift = 32 - logN;
+    // bin k of the real spectrum from the half-length transform: X_k = E_k + w^k O_k with E, O the transforms of
+    // the even and odd samples, both read off Z[k] and conj(Z[N-k]) (stored bit-reversed)
+    int kstar = (int)floor(cutoff_frac * (double)N);            // N = floor(L/2) = n_bins - 1
+    if (g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION) {
+        auto bin_energy = [&](int k) -> float {
+            if (k == 0 || k == N) {
+                const cf z0 = z[0];
+                const float x = k == 0 ? z0.re + z0.im : z0.re - z0.im;
+                return x * x;
+            }
+            const cf A = z[pad((int)(__brev((unsigned)k) >> shift))];
+            const cf B = cconj(z[pad((int)(__brev((unsigned)(N - k)) >> shift))]);
+            const cf E = {0.5f * (A.re + B.re), 0.5f * (A.im + B.im)};
+            const cf Dm = csub(A, B);
+            const cf O = {0.5f * Dm.im, -0.5f * Dm.re};
+            const cf X = cadd(E, cmul(twiddle(lo, hi, k), O));
+            return X.re * X.re + X.im * X.im;
+        };
+        EnergyScratch* sc = reinterpret_cast<EnergyScratch*>(hi + n_hi + 1);
+        kstar = energy_cutoff(bin_energy, N + 1, g.cutoff_mode == AUDIOKV_CUTOFF_ENERGY_NO_DC ? 1 : 0, cutoff_frac, sc);
+    }
+    if (kstar_out && tid == 0) kstar_out[head] = kstar;
+    if (cutoffs_only) return;
+
+    // low-pass mask (Eq. 17-18) and back to the half-length form, pair (k, N-k) at a time
+    const int ktop = kstar + T;                                 // last bin with a non-zero weight
     for (int k = tid; k <= (N >> 1); k += kFftThreads) {
         if (k == 0) {
             const cf z0 = z[0];
             const float X0 = z0.re + z0.im;                     // DC bin, always kept (0 <= k*)
-            const float XN = (N <= kstar) ? (z0.re - z0.im) : 0.f;   // Nyquist bin
+            const float XN = (z0.re - z0.im) * mask_weight(N, kstar, T);   // Nyquist bin
             z[0] = {0.5f * (X0 + XN), 0.5f * (X0 - XN)};
             continue;
         }
         const int pa = pad(logN ? (int)(__brev((unsigned)k) >> shift) : 0);
         const int pb = pad(logN ? (int)(__brev((unsigned)(N - k)) >> shift) : 0);
-        if (k > kstar && N - k > kstar) {                       // both bins masked
+        if (k > ktop && N - k > ktop) {                         // both bins masked
             z[pa] = {0.f, 0.f};
             z[pb] = {0.f, 0.f};
             continue;
@@ -263,8 +342,9 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
         const cf WO = cmul(Wk, O);
         cf Xk = cadd(E, WO);                                    // bin k
         cf Xn = cconj(csub(E, WO));                             // bin N - k
-        if (k > kstar) Xk = {0.f, 0.f};
-        if (N - k > kstar) Xn = {0.f, 0.f};
+        const float wk = mask_weight(k, kstar, T), wn = mask_weight(N - k, kstar, T);
+        Xk = {Xk.re * wk, Xk.im * wk};
+        Xn = {Xn.re * wn, Xn.im * wn};
         const cf Xnc = cconj(Xn);
         const cf E2 = {0.5f * (Xk.re + Xnc.re), 0.5f * (Xk.im + Xnc.im)};
         const cf H2 = {0.5f * (Xk.re - Xnc.re), 0.5f * (Xk.im - Xnc.im)};
@@ -357,7 +437,8 @@ __device__ __noinline__ void fft_pass(cf* __restrict__ x, int logM, bool inverse
 
 __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
-    double cutoff_frac, float alpha, float* __restrict__ out, cf* __restrict__ ws, size_t ws_stride)
+    double cutoff_frac, float alpha, float* __restrict__ out, cf* __restrict__ ws, size_t ws_stride,
+    int32_t* __restrict__ kstar_out, int cutoffs_only)
 {
     extern __shared__ float smem[];
     const int head = blockIdx.x;
@@ -369,6 +450,11 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const float* src = in + off;
     float* dst = out + off;
     const int tid = threadIdx.x;
+    const int T = g.taper_bins;
+    if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && cutoffs_only) {
+        if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
+        return;
+    }
     const int logM = bluestein_log(L);
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
@@ -409,16 +495,29 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
 
     // F_k = chirp(k) * A[k] / M; low-pass mask on the two-sided bin index (Eq. 17-18); the inverse transform is
     // the conjugate of a forward transform of conj(F~), so feed conj(F~) * chirp into the same machinery
-    const int kstar = (int)floor(cutoff_frac * (double)(L >> 1));
+    int kstar = (int)floor(cutoff_frac * (double)(L >> 1));
     const float inv_m = 1.0f / (float)M;
+    if (g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION) {
+        // |F_k| = |A[k]| / M: the chirp has unit modulus
+        auto bin_energy = [&](int k) -> float {
+            const cf a = A[k];
+            const float re = a.re * inv_m, im = a.im * inv_m;
+            return re * re + im * im;
+        };
+        EnergyScratch* sc = reinterpret_cast<EnergyScratch*>(hi + n_hi + 1);
+        kstar = energy_cutoff(bin_energy, (L >> 1) + 1, g.cutoff_mode == AUDIOKV_CUTOFF_ENERGY_NO_DC ? 1 : 0, cutoff_frac, sc);
+    }
+    if (kstar_out && tid == 0) kstar_out[head] = kstar;
+    if (cutoffs_only) return;
     for (int k = tid; k < M; k += kFftThreads) {
         cf v = {0.f, 0.f};
         if (k < L) {
             const int bin = k < L - k ? k : L - k;
-            if (bin <= kstar) {
+            const float wgt = mask_weight(bin, kstar, T);
+            if (wgt > 0.f) {
                 const cf w = chirp(k, L);
                 cf F = cmul(w, A[k]);
-                F = {F.re * inv_m, F.im * inv_m};
+                F = {F.re * inv_m * wgt, F.im * inv_m * wgt};
                 v = cmul(cconj(F), w);
             }
         }
@@ -466,8 +565,10 @@ size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv
 
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, void* workspace, hipStream_t s)
+                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s)
 {
+    if (cutoffs_only && !kstar_out) return hipErrorInvalidValue;
+    const size_t extra = g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION ? sizeof(EnergyScratch) + 2 * sizeof(cf) : 0;
     int max_pow2 = 0, max_log = 0;
     for (int i = 0; i < n_items; ++i) {
         if (pow2_length(seqlens_host[i])) max_pow2 = max(max_pow2, seqlens_host[i]);
@@ -487,18 +588,18 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
     // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
     if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
         const int n_hi = (max_pow2 >> 8) + 1;
-        const size_t smem = (padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf);
+        const size_t smem = (padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf) + extra;
         hipLaunchKernelGGL(smooth_pow2_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
-                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out);
+                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, kstar_out, cutoffs_only ? 1 : 0);
     }
     if (max_log > 0 && alpha != 0.0) {
         if (!workspace) return hipErrorInvalidValue;
         const size_t M = (size_t)1 << max_log;
         const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
-        const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf);
+        const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out,
-                           static_cast<cf*>(workspace), 2 * M);
+                           static_cast<cf*>(workspace), 2 * M, kstar_out, cutoffs_only ? 1 : 0);
     }
     return hipGetLastError();
 }
