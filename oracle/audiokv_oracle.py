@@ -26,9 +26,13 @@ What it computes (paper: AudioKV, Sec. 3):
   compact   gather the retained K/V rows into a packed cache (Sec. 1: the
             cache keeps only salient tokens; Sec. 4.6: memory follows the
             retention ratio).
+  decode_attend  what the next decoding step does with that cache: each query
+            head attends to the retained rows of its KV head only (plain
+            scaled-dot-product attention over b_h rows; the definition itself).
 
 The method is a heuristic pipeline rather than a fast route to a textbook
-quantity, so each function takes the steps in the paper's order, in float64.
+quantity, so each function takes the steps in the paper's order, in float64
+(decode_attend alone has a plain definition, and is that definition).
 The DFTs are written as direct sums (no FFT library); because every bin above
 k* is zeroed, the direct sums cost only O(L * k*).
 
@@ -42,8 +46,8 @@ tokens per head; largest-remainder integerisation; n_keep = floor(ratio*L+.5).
 Parity status: no function here can be pinned to a number printed in the
 paper (it prints none for this path). They are pinned by closed forms,
 invariants, brute force on tiny inputs and library cross-checks in
-tests/test_oracle_*.py. The value of the uniform floor fraction beta and the
-cosine taper (not implemented) are "parity unpinned".
+tests/test_oracle_*.py. The value of the uniform floor fraction beta, and the
+shape and width of the cosine taper, are "parity unpinned".
 """
 
 from __future__ import annotations
@@ -66,6 +70,7 @@ __all__ = [
     "smooth",
     "select",
     "compact",
+    "decode_attend",
     "evict_item",
 ]
 
@@ -385,6 +390,35 @@ def compact(k: np.ndarray, v: np.ndarray, indices: List[np.ndarray]) -> Tuple[np
     ko = [k[h][np.asarray(ix, dtype=np.int64)] for h, ix in enumerate(indices)]
     vo = [v[h][np.asarray(ix, dtype=np.int64)] for h, ix in enumerate(indices)]
     return np.concatenate(ko, axis=0), np.concatenate(vo, axis=0)
+
+
+# ---------------------------------------------------------------------------
+# After the path: one decoding step on the compacted cache
+# ---------------------------------------------------------------------------
+
+def decode_attend(q: np.ndarray, k_rows: Sequence[np.ndarray], v_rows: Sequence[np.ndarray], *,
+                  scale: Optional[float] = None) -> np.ndarray:
+    """Single-query attention of every query head over the retained rows of its
+    KV head (Sec. 1 / Sec. 4.6: decoding runs on the compressed cache).
+    q: [H_q, d]; k_rows[h], v_rows[h]: [b_h, d] for KV head h (b_h >= 1);
+    query head j reads KV head j // (H_q / H_kv). Returns [H_q, d] float64:
+    out_j = sum_t softmax_t(scale * <q_j, K_h[t]>) * V_h[t]."""
+    q = np.asarray(q, dtype=np.float64)
+    H_q, d = q.shape
+    H_kv = len(k_rows)
+    assert H_q % H_kv == 0 and len(v_rows) == H_kv
+    G = H_q // H_kv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((H_q, d), dtype=np.float64)
+    for j in range(H_q):
+        K = np.asarray(k_rows[j // G], dtype=np.float64)
+        V = np.asarray(v_rows[j // G], dtype=np.float64)
+        z = scale * (K @ q[j])
+        z = z - z.max()
+        e = np.exp(z)
+        out[j] = (e / e.sum()) @ V
+    return out
 
 
 # ---------------------------------------------------------------------------
