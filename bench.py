@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--cutoff", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the timing of the decode-side consumer")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
@@ -218,6 +219,29 @@ def main():
         "compact_GBs": ab["compact"] / (stage_ms["compact"] * 1e-3) / 1e9,
         "roofline": roof,
     }
+    if not args.no_decode:
+        # the step after the path: one decoding step (one new query per head) over the compacted cache just written
+        qd = torch.randn(cfg.n_items * cfg.n_q_heads * cfg.head_dim, device=dev).to(torch.bfloat16)
+        n_rows = kept * cfg.n_kv_heads
+        dws = torch.empty(A.decode_workspace_bytes(p, cfg.n_items, n_rows), dtype=torch.uint8, device=dev)
+        dout = torch.empty((cfg.n_items, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=dev)
+
+        def dstep():
+            A.decode_attend(p, qd, outs["k_out"], outs["v_out"], outs["cu_budgets"], cfg.n_items, n_rows,
+                            out=dout, workspace=dws)
+        for _ in range(3):
+            dstep()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            dstep()
+        e1.record()
+        torch.cuda.synchronize()
+        d_ms = e0.elapsed_time(e1) / args.steps
+        d_bytes = 2 * kept * cfg.n_kv_heads * cfg.head_dim * 2          # every retained K and V row once
+        res["decode_consumer"] = {"ms_per_step": d_ms, "algorithmic_bytes": d_bytes, "GBs": d_bytes / d_ms / 1e6,
+                                  "hbm_frac": d_bytes / d_ms / 1e6 / HBM_PEAK_GBS,
+                                  "what": "single-query attention of all query heads over the compacted cache of all layers"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, item0, w_host, lens[0], cfg.ratio, cfg.cutoff, cfg.alpha)
     print(json.dumps(res))

@@ -233,6 +233,25 @@ int32_t audiokv_evict(const audiokv_params* params,
                       int32_t* budgets_dev, int32_t* cu_budgets_dev,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* The step after the path: one decoding step on the compacted cache (paper
+ * Sec. 1 and Sec. 4.6: generation proceeds on the retained tokens only).
+ * q_dev: bf16 [n_items][n_q_heads][head_dim], one new query per head;
+ * k_cache / v_cache / cu_budgets_dev: as written by audiokv_compact /
+ * audiokv_evict. out_dev: fp32 [n_items][n_q_heads][head_dim],
+ *   out[i][j] = sum_t softmax_t(scale * <q[i][j], K_g[t]>) * V_g[t]
+ * over the budgets[g] rows of KV head g = i * n_kv_heads + j / (n_q_heads /
+ * n_kv_heads). total_rows (host) is the sum of all budgets
+ * (audiokv_total_kept): it sizes the launch and the workspace
+ * (audiokv_decode_workspace_bytes); cache rows at or beyond total_rows are
+ * never read. A head with budget 0 yields zeros. n_q_heads / n_kv_heads <= 16. */
+int32_t audiokv_decode_workspace_bytes(const audiokv_params* params, int32_t n_items, int64_t total_rows,
+                                       size_t* out_bytes);
+int32_t audiokv_decode_attend(const audiokv_params* params,
+                              const void* q_dev, const void* k_cache, const void* v_cache,
+                              const int32_t* cu_budgets_dev, int32_t n_items, int64_t total_rows,
+                              float* out_dev,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aid, not part of the method (used by the benchmark to time the
  * kernels of audiokv_evict where they run). While enabled, audiokv_evict records
  * HIP events on the caller's stream between its kernels; audiokv_profile_read

@@ -91,11 +91,14 @@ def _load() -> C.CDLL:
     lib.audiokv_compact.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.audiokv_evict.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
                                   vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.audiokv_decode_workspace_bytes.argtypes = [pp, i32, i64, C.POINTER(C.c_size_t)]
+    lib.audiokv_decode_attend.argtypes = [pp, vp, vp, vp, vp, i32, i64, vp, vp, C.c_size_t, vp]
     lib.audiokv_profile_enable.argtypes = [i32]
     lib.audiokv_profile_enable.restype = i32
     lib.audiokv_profile_read.argtypes = [C.POINTER(C.c_float)]
     lib.audiokv_profile_read.restype = i32
-    for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "smooth_cutoffs", "select", "compact", "evict"):
+    for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "smooth_cutoffs", "select", "compact", "evict",
+                 "decode_workspace_bytes", "decode_attend"):
         getattr(lib, "audiokv_" + name).restype = i32
     return lib
 
@@ -278,6 +281,30 @@ def evict(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weig
     o["total_rows"] = rows
     o["workspace"] = ws
     return o
+
+
+def decode_workspace_bytes(p: Params, n_items: int, total_rows: int) -> int:
+    out = C.c_size_t(0)
+    cp = p.c()
+    _check(_lib.audiokv_decode_workspace_bytes(C.byref(cp), int(n_items), int(total_rows), C.byref(out)))
+    return out.value
+
+
+def decode_attend(p: Params, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                  cu_budgets: torch.Tensor, n_items: int, total_rows: int, *,
+                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decoding step on the compacted cache: fp32 [n_items, n_q_heads, head_dim]."""
+    _need(q, torch.bfloat16, "q"); _need(k_cache, torch.bfloat16, "k_cache"); _need(v_cache, torch.bfloat16, "v_cache")
+    _need(cu_budgets, torch.int32, "cu_budgets")
+    dev = q.device
+    if out is None:
+        out = torch.empty((n_items, p.n_q_heads, p.head_dim), dtype=torch.float32, device=dev)
+    need = decode_workspace_bytes(p, n_items, total_rows)
+    ws = workspace if workspace is not None else torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    cp = p.c()
+    _check(_lib.audiokv_decode_attend(C.byref(cp), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(cu_budgets),
+                                      int(n_items), int(total_rows), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+    return out
 
 
 PROFILE_STAGES = ("allocate", "score_sweep1", "score_sweep2", "pool_smooth", "select", "compact")

@@ -458,6 +458,38 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     return AUDIOKV_OK;
 }
 
+int32_t audiokv_decode_workspace_bytes(const audiokv_params* params, int32_t n_items, int64_t total_rows,
+                                       size_t* out_bytes)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    if (!out_bytes || n_items < 1 || total_rows < 0 || total_rows > (int64_t)INT32_MAX)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_decode_workspace_bytes: NULL pointer, n_items < 1 or total_rows out of range");
+    *out_bytes = decode_workspace_bytes(make_geom(params, n_items), total_rows);
+    return AUDIOKV_OK;
+}
+
+int32_t audiokv_decode_attend(const audiokv_params* params, const void* q_dev, const void* k_cache,
+                              const void* v_cache, const int32_t* cu_budgets_dev, int32_t n_items,
+                              int64_t total_rows, float* out_dev, void* workspace, size_t workspace_bytes,
+                              void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 0));
+    if (!q_dev || !k_cache || !v_cache || !cu_budgets_dev || !out_dev || !workspace)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_decode_attend: NULL pointer argument");
+    if (n_items < 1 || total_rows < 0 || total_rows > (int64_t)INT32_MAX)
+        return fail(AUDIOKV_E_INVALID_ARG, "n_items must be >= 1 and total_rows in [0, 2^31)");
+    if (!decode_supported(params->n_q_heads / params->n_kv_heads))
+        return fail(AUDIOKV_E_UNSUPPORTED, "decode: %d query heads per KV head > 16", params->n_q_heads / params->n_kv_heads);
+    const Geom g = make_geom(params, n_items);
+    const size_t need = decode_workspace_bytes(g, total_rows);
+    if (workspace_bytes < need)
+        return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    AUDIOKV_HIP(launch_decode(g, q_dev, k_cache, v_cache, cu_budgets_dev, total_rows, out_dev, workspace,
+                              static_cast<hipStream_t>(stream)),
+                "decode kernels");
+    return AUDIOKV_OK;
+}
+
 int32_t audiokv_profile_enable(int32_t enable)
 {
     if (enable && !g_prof.created) {

@@ -62,6 +62,12 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
                          float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s);
 
+// single-query attention over the packed cache
+bool decode_supported(int G);
+size_t decode_workspace_bytes(const Geom& g, long long total_rows);
+hipError_t launch_decode(const Geom& g, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* cu_budgets, long long total_rows, float* out, void* workspace, hipStream_t s);
+
 bool select_supported(int L);
 hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budgets, const int32_t* cu_budgets,
                          const int32_t* cu_seqlens, int max_L, int32_t* indices, hipStream_t s);
