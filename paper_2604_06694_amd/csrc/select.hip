@@ -7,7 +7,8 @@
 // The value of the k-th largest key is found bit by bit (32 counting passes,
 // no atomics); tokens above it are kept, tokens equal to it are kept in index
 // order until the budget is full, and kept indices are written in ascending
-// order through a block-wide exclusive scan. Integer-only: bit-exact.
+// order through a block-wide exclusive scan (gathered in LDS, stored coalesced).
+// Integer-only: bit-exact.
 #include "common.h"
 
 namespace audiokv {
@@ -101,10 +102,17 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int parity = 0;
     for (int bit = 31; bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
+        // wave-wide count on the scalar unit: one compare per key, its lane mask counted with a population count
         int c = 0;
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) c += key[e] >= trial ? 1 : 0;
-        if (block_count(c, slots, parity) >= want) T = trial;
+        for (int e = 0; e < EPT; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= trial));
+        int* sl = slots + parity * kSelWaves;
+        if ((tid & 63) == 0) sl[tid >> 6] = c;
+        __syncthreads();
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) t += sl[w];
+        if (t >= want) T = trial;
         parity ^= 1;
     }
     // tokens strictly above T all stay; tokens equal to T stay in index order while room is left
@@ -121,18 +129,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int total_gt = block_count(c_gt, slots, parity);
     const int need_eq = want - total_gt;             // >= 1 by construction of T
 
+    // Kept indices are gathered in LDS at their output slots (the staging buffer is free: the keys live in
+    // registers) and then written out in one coalesced sweep; written straight from here, every store of a wave
+    // would touch 64 different cache lines.
+    int32_t* lds_out = reinterpret_cast<int32_t*>(stage);
+    __syncthreads();                                 // all reads of the staged scores are long done; be explicit
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         const int j = tid * EPT + e;
         if (j >= n_cand) break;
         if (key[e] > T) {
-            out[gt_before + min(eq_before, need_eq)] = j;
+            lds_out[gt_before + min(eq_before, need_eq)] = j;
             ++gt_before;
         } else if (key[e] == T) {
-            if (eq_before < need_eq) out[gt_before + eq_before] = j;
+            if (eq_before < need_eq) lds_out[gt_before + eq_before] = j;
             ++eq_before;
         }
     }
+    __syncthreads();
+    for (int t = tid; t < want; t += kSelThreads) out[t] = lds_out[t];
 }
 
 }  // namespace
