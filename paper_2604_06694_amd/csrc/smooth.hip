@@ -34,7 +34,7 @@ __device__ __forceinline__ float pooled_at(const float* x, int L, int j, int ker
             const int p = j + t;
             acc += (p >= 0 && p < L) ? x[p] : 0.f;       // zero padding
         }
-        return acc / (float)kernel;                       // divisor is always the kernel size
+        return acc * (1.0f / (float)kernel);              // divisor is always the kernel size (one rounded reciprocal)
     }
     float acc = -INFINITY;
     for (int t = -half; t <= half; ++t) {
@@ -42,6 +42,33 @@ __device__ __forceinline__ float pooled_at(const float* x, int L, int j, int ker
         if (p >= 0 && p < L) acc = fmaxf(acc, x[p]);
     }
     return acc;
+}
+
+// Pooled values at positions j0 and j0 + 1 of a sequence held in LDS, kernel size K known at compile time. Same
+// taps, padding, order of operations and reciprocal as pooled_at, so both give the same bits.
+template <int K>
+__device__ __forceinline__ void pooled_pair_lds(const float* x, int L, int j0, int mode, float& o0, float& o1) {
+    const float fill = mode == AUDIOKV_POOL_AVG ? 0.f : -INFINITY;
+    float w[K + 1];
+#pragma unroll
+    for (int u = 0; u <= K; ++u) {
+        const int p = j0 - K / 2 + u;
+        const float v = x[min(max(p, 0), L - 1)];
+        w[u] = (p >= 0 && p < L) ? v : fill;
+    }
+    if (mode == AUDIOKV_POOL_AVG) {
+        float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+        for (int u = 0; u < K; ++u) { a0 += w[u]; a1 += w[u + 1]; }
+        o0 = a0 * (1.0f / (float)K);
+        o1 = a1 * (1.0f / (float)K);
+    } else {
+        float a0 = -INFINITY, a1 = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < K; ++u) { a0 = fmaxf(a0, w[u]); a1 = fmaxf(a1, w[u + 1]); }
+        o0 = a0;
+        o1 = a1;
+    }
 }
 
 __global__ __launch_bounds__(256) void pool_kernel(Geom g, const float* __restrict__ raw,
@@ -268,16 +295,44 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     cf* hi = lo + kTwLo;                          // (L/2)/128 + 1 entries: w^(128 j)
     const int n_hi = (N >> 7) + 1;
 
-    for (int i = tid; i < N; i += kFftThreads) {
-        cf v;
-        if (pool_on_load) {
-            v.re = pooled_at(src, L, 2 * i, g.pool_kernel, g.pool_mode);
-            v.im = pooled_at(src, L, 2 * i + 1, g.pool_kernel, g.pool_mode);
-        } else {
-            v.re = src[2 * i];
-            v.im = src[2 * i + 1];
+    if (pool_on_load) {
+        // one coalesced read of the raw scores into LDS, pooling from there (every tap from global memory would
+        // cost kernel-size times the loads), pooled values parked in registers while the buffer changes layout
+        float* rawf = smem;
+        for (int j = tid; j < L; j += 8 * kFftThreads) {         // eight loads in flight per thread
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = src[min(j + u * kFftThreads, L - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j + u * kFftThreads < L) rawf[j + u * kFftThreads] = t[u];
         }
-        z[pad(i)] = v;
+        __syncthreads();
+        constexpr int kPer = (kMaxPow2L / 2) / kFftThreads;      // complex points per thread at the longest L
+        cf keep[kPer];
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            const int i = tid + e * kFftThreads;
+            if (i < N) {
+                switch (g.pool_kernel) {
+                    case 3:  pooled_pair_lds<3>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
+                    case 5:  pooled_pair_lds<5>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
+                    case 7:  pooled_pair_lds<7>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
+                    case 9:  pooled_pair_lds<9>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
+                    default:
+                        keep[e].re = pooled_at(rawf, L, 2 * i, g.pool_kernel, g.pool_mode);
+                        keep[e].im = pooled_at(rawf, L, 2 * i + 1, g.pool_kernel, g.pool_mode);
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            const int i = tid + e * kFftThreads;
+            if (i < N) z[pad(i)] = keep[e];
+        }
+    } else {
+        for (int i = tid; i < N; i += kFftThreads) z[pad(i)] = {src[2 * i], src[2 * i + 1]};
     }
     for (int t = tid; t < kTwLo + n_hi; t += kFftThreads) {
         const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
@@ -316,18 +371,24 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     if (kstar_out && tid == 0) kstar_out[head] = kstar;
     if (cutoffs_only) return;
 
-    // low-pass mask (Eq. 17-18) and back to the half-length form, pair (k, N-k) at a time
+    // low-pass mask (Eq. 17-18) and back to the half-length form, pair (k, N-k) at a time. The transform sits in
+    // bit-reversed order, so the loop runs over storage slots, not bins: slot p holds bin brev(p), consecutive
+    // lanes touch consecutive slots (bins in natural order would put a whole wave on one LDS bank), and the
+    // partner slot brev(N - k) runs backwards through consecutive slots as well. Bins 1..N/2-1 are exactly the
+    // even slots (their top bit is clear); slot 0 is bin 0 (with the Nyquist bin folded into it), slot 1 is bin N/2.
     const int ktop = kstar + T;                                 // last bin with a non-zero weight
-    for (int k = tid; k <= (N >> 1); k += kFftThreads) {
-        if (k == 0) {
+    for (int q = tid; q < (N >> 1) + 1; q += kFftThreads) {
+        if (q == 0) {
             const cf z0 = z[0];
             const float X0 = z0.re + z0.im;                     // DC bin, always kept (0 <= k*)
             const float XN = (z0.re - z0.im) * mask_weight(N, kstar, T);   // Nyquist bin
             z[0] = {0.5f * (X0 + XN), 0.5f * (X0 - XN)};
             continue;
         }
-        const int pa = pad(logN ? (int)(__brev((unsigned)k) >> shift) : 0);
-        const int pb = pad(logN ? (int)(__brev((unsigned)(N - k)) >> shift) : 0);
+        const int slot = q == (N >> 1) ? 1 : 2 * q;             // the extra trip takes the self-paired bin N/2
+        const int k = (int)(__brev((unsigned)slot) >> shift);
+        const int pa = pad(slot);
+        const int pb = pad((int)(__brev((unsigned)(N - k)) >> shift));
         if (k > ktop && N - k > ktop) {                         // both bins masked
             z[pa] = {0.f, 0.f};
             z[pb] = {0.f, 0.f};
