@@ -441,26 +441,39 @@ __global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
     }
 }
 
-// per row: max + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes
-static __global__ __launch_bounds__(256) void score_merge_kernel(const float* __restrict__ stats, int nsplit,
-                                                                 int rows_pad, int R, float* __restrict__ cst)
+// per row: max + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes.
+// One thread per row, 64 rows per workgroup. The per-range statistics are fetched eight at a time so that the
+// loads overlap instead of forming a chain of memory latencies as long as the number of ranges.
+static __global__ __launch_bounds__(64) void score_merge_kernel(const float* __restrict__ stats, int nsplit,
+                                                                int rows_pad, int R, float* __restrict__ cst)
 {
-    const int head = blockIdx.x;
-    const float* hs = stats + (size_t)head * nsplit * rows_pad * 2;
-    for (int r = threadIdx.x; r < rows_pad; r += blockDim.x) {
-        float out = INFINITY;
-        if (r < R) {
-            float M = -INFINITY;
-            for (int s = 0; s < nsplit; ++s) M = fmaxf(M, hs[((size_t)s * rows_pad + r) * 2]);
-            float Z = 0.f;
-            for (int s = 0; s < nsplit; ++s) {
-                const float ms = hs[((size_t)s * rows_pad + r) * 2], ls = hs[((size_t)s * rows_pad + r) * 2 + 1];
-                if (ls > 0.f) Z += ls * fast_exp2(ms - M);
-            }
-            out = M + __log2f(Z);
+    const int blocks_per_head = (rows_pad + 63) / 64;
+    const int head = blockIdx.x / blocks_per_head;
+    const int r = (blockIdx.x - head * blocks_per_head) * 64 + threadIdx.x;
+    if (r >= rows_pad) return;
+    float out = INFINITY;
+    if (r < R) {
+        const float2* hs = reinterpret_cast<const float2*>(stats) + (size_t)head * nsplit * rows_pad + r;
+        float M = -INFINITY;
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) M = fmaxf(M, v[u].x);
         }
-        cst[(size_t)head * rows_pad + r] = out;
+        float Z = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < nsplit && v[u].y > 0.f) Z += v[u].y * fast_exp2(v[u].x - M);
+        }
+        out = M + __log2f(Z);
     }
+    cst[(size_t)head * rows_pad + r] = out;
 }
 
 template <int D, int NB, int WR>
@@ -483,8 +496,8 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
     }
     hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
                        (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, (const float*)nullptr, raw);
-    hipLaunchKernelGGL(score_merge_kernel, dim3(n_heads), dim3(256), 0, s, (const float*)stats, nsplit, T::ROWS,
-                       g.G * g.W, cst);
+    hipLaunchKernelGGL(score_merge_kernel, dim3((unsigned)(n_heads * ((T::ROWS + 63) / 64))), dim3(64), 0, s,
+                       (const float*)stats, nsplit, T::ROWS, g.G * g.W, cst);
     if (between) {
         const hipError_t e = hipEventRecord(between, s);
         if (e != hipSuccess) return e;
