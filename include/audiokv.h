@@ -129,6 +129,20 @@ int32_t audiokv_score(const audiokv_params* params,
                       float* scores,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* Stage 1 when the row statistics already exist (same passage as
+ * audiokv_score). The prefill attention kernel that ran the last `window`
+ * queries normally returns, per query row, the log-sum-exp of its scaled
+ * logits; given those, the first of the two passes over K (which only
+ * rebuilds them) is skipped. lse_dev: fp32 [n_items][n_q_heads][window],
+ * natural log of sum_j exp(scale * <q, K[j]>) over the keys the row may see
+ * (the same mask and scale as params). Everything else as audiokv_score; the
+ * scores match audiokv_score to the accuracy of the supplied values. */
+int32_t audiokv_score_lse(const audiokv_params* params,
+                          const void* q_win, const void* k, const float* lse_dev,
+                          const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                          float* scores,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Stage 2 - head-wise budget allocation (paper Sec. 3.1 Eq. 1:
  * b = w + r + B_score * S / sum S; Sec. 3.2 Eq. 12: floor of the proportional
  * share), made to sum exactly to the pool total.
@@ -232,6 +246,17 @@ int32_t audiokv_evict(const audiokv_params* params,
                       void* k_out, void* v_out, int32_t* indices_dev,
                       int32_t* budgets_dev, int32_t* cu_budgets_dev,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* audiokv_evict with the window rows' log-sum-exp supplied (see
+ * audiokv_score_lse): identical otherwise, one pass over K instead of two. */
+int32_t audiokv_evict_lse(const audiokv_params* params,
+                          const void* q_win, const void* k, const void* v, const float* lse_dev,
+                          const float* weights_dev, int32_t alloc_scope,
+                          const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                          double ratio, double cutoff_frac, double alpha,
+                          void* k_out, void* v_out, int32_t* indices_dev,
+                          int32_t* budgets_dev, int32_t* cu_budgets_dev,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* The step after the path: one decoding step on the compacted cache (paper
  * Sec. 1 and Sec. 4.6: generation proceeds on the retained tokens only).

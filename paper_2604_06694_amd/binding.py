@@ -84,12 +84,15 @@ def _load() -> C.CDLL:
     lib.audiokv_total_kept.argtypes = [pp, i32, vp, f64, C.POINTER(i64)]
     lib.audiokv_workspace_bytes.argtypes = [pp, i32, vp, C.POINTER(C.c_size_t)]
     lib.audiokv_score.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
+    lib.audiokv_score_lse.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.audiokv_allocate.argtypes = [pp, vp, i32, i32, i32, vp, vp, f64, vp, vp, vp]
     lib.audiokv_smooth.argtypes = [pp, vp, vp, vp, i32, f64, f64, vp, vp, C.c_size_t, vp]
     lib.audiokv_smooth_cutoffs.argtypes = [pp, vp, vp, vp, i32, f64, vp, vp, C.c_size_t, vp]
     lib.audiokv_select.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.audiokv_compact.argtypes = [pp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.audiokv_evict.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
+                                  vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.audiokv_evict_lse.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
                                   vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.audiokv_decode_workspace_bytes.argtypes = [pp, i32, i64, C.POINTER(C.c_size_t)]
     lib.audiokv_decode_attend.argtypes = [pp, vp, vp, vp, vp, i32, i64, vp, vp, C.c_size_t, vp]
@@ -98,7 +101,7 @@ def _load() -> C.CDLL:
     lib.audiokv_profile_read.argtypes = [C.POINTER(C.c_float)]
     lib.audiokv_profile_read.restype = i32
     for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "smooth_cutoffs", "select", "compact", "evict",
-                 "decode_workspace_bytes", "decode_attend"):
+                 "decode_workspace_bytes", "decode_attend", "score_lse", "evict_lse"):
         getattr(lib, "audiokv_" + name).restype = i32
     return lib
 
@@ -168,7 +171,9 @@ def _workspace(p: Params, seqlens: Sequence[int], device, workspace: Optional[to
 
 def score(p: Params, q_win: torch.Tensor, k: torch.Tensor, seqlens: Sequence[int], *,
           cu_seqlens: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+          workspace: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """`lse` (fp32 [n_items, n_q_heads, window], natural-log softmax denominators of the window rows) selects
+    audiokv_score_lse."""
     _need(q_win, torch.bfloat16, "q_win"); _need(k, torch.bfloat16, "k")
     dev = k.device
     cu = cu_seqlens if cu_seqlens is not None else _cu(seqlens, dev)
@@ -177,6 +182,11 @@ def score(p: Params, q_win: torch.Tensor, k: torch.Tensor, seqlens: Sequence[int
         out = torch.empty(total, dtype=torch.float32, device=dev)
     ws = _workspace(p, seqlens, dev, workspace)
     cp = p.c()
+    if lse is not None:
+        _need(lse, torch.float32, "lse")
+        _check(_lib.audiokv_score_lse(C.byref(cp), _ptr(q_win), _ptr(k), _ptr(lse), _ptr(cu), _host_lens(seqlens),
+                                      len(seqlens), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
     _check(_lib.audiokv_score(C.byref(cp), _ptr(q_win), _ptr(k), _ptr(cu), _host_lens(seqlens), len(seqlens),
                               _ptr(out), _ptr(ws), ws.numel(), _stream()))
     return out
@@ -256,8 +266,9 @@ def compact(p: Params, k: torch.Tensor, v: torch.Tensor, indices: torch.Tensor, 
 def evict(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weights: torch.Tensor,
           seqlens: Sequence[int], ratio: float, cutoff_frac: float, alpha: float, *,
           alloc_scope: int = SCOPE_GLOBAL, cu_seqlens: Optional[torch.Tensor] = None,
-          workspace: Optional[torch.Tensor] = None, outputs: Optional[dict] = None) -> dict:
-    """Runs the fused path. `outputs` may carry preallocated k_out, v_out, indices, budgets, cu_budgets
+          workspace: Optional[torch.Tensor] = None, outputs: Optional[dict] = None,
+          lse: Optional[torch.Tensor] = None) -> dict:
+    """Runs the fused path (audiokv_evict_lse when `lse` is given). `outputs` may carry preallocated k_out, v_out, indices, budgets, cu_budgets
     (used by the benchmark so that the timed region allocates nothing)."""
     _need(q_win, torch.bfloat16, "q_win"); _need(k, torch.bfloat16, "k"); _need(v, torch.bfloat16, "v")
     _need(weights, torch.float32, "weights")
@@ -274,6 +285,16 @@ def evict(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weig
         o["cu_budgets"] = torch.empty(n_heads + 1, dtype=torch.int32, device=dev)
     ws = _workspace(p, seqlens, dev, workspace)
     cp = p.c()
+    if lse is not None:
+        _need(lse, torch.float32, "lse")
+        _check(_lib.audiokv_evict_lse(C.byref(cp), _ptr(q_win), _ptr(k), _ptr(v), _ptr(lse), _ptr(weights),
+                                      int(alloc_scope), _ptr(cu), _host_lens(seqlens), len(seqlens), float(ratio),
+                                      float(cutoff_frac), float(alpha), _ptr(o["k_out"]), _ptr(o["v_out"]),
+                                      _ptr(o["indices"]), _ptr(o["budgets"]), _ptr(o["cu_budgets"]), _ptr(ws),
+                                      ws.numel(), _stream()))
+        o["total_rows"] = rows
+        o["workspace"] = ws
+        return o
     _check(_lib.audiokv_evict(C.byref(cp), _ptr(q_win), _ptr(k), _ptr(v), _ptr(weights), int(alloc_scope), _ptr(cu),
                               _host_lens(seqlens), len(seqlens), float(ratio), float(cutoff_frac), float(alpha),
                               _ptr(o["k_out"]), _ptr(o["v_out"]), _ptr(o["indices"]), _ptr(o["budgets"]),

@@ -239,9 +239,10 @@ int32_t audiokv_workspace_bytes(const audiokv_params* params, int32_t n_items, c
     return AUDIOKV_OK;
 }
 
-int32_t audiokv_score(const audiokv_params* params, const void* q_win, const void* k,
-                      const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
-                      float* scores, void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+int32_t score_entry(const audiokv_params* params, const void* q_win, const void* k, const float* lse_dev,
+                    const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                    float* scores, void* workspace, size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 1));
     Batch b;
@@ -258,10 +259,28 @@ int32_t audiokv_score(const audiokv_params* params, const void* q_win, const voi
     char* ws = static_cast<char*>(workspace);
     float* stats = reinterpret_cast<float*>(ws + w.stats_off);
     float* raw = params->pool_kernel == 1 ? scores : reinterpret_cast<float*>(ws + w.raw_off);
-    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s), "score kernels");
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s, nullptr, lse_dev), "score kernels");
     if (params->pool_kernel != 1)
         AUDIOKV_HIP(launch_pool(g, raw, cu_seqlens_dev, b.max_L, scores, s), "pool kernel");
     return AUDIOKV_OK;
+}
+}  // namespace
+
+int32_t audiokv_score(const audiokv_params* params, const void* q_win, const void* k,
+                      const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                      float* scores, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return score_entry(params, q_win, k, nullptr, cu_seqlens_dev, seqlens_host, n_items, scores, workspace,
+                       workspace_bytes, stream);
+}
+
+int32_t audiokv_score_lse(const audiokv_params* params, const void* q_win, const void* k, const float* lse_dev,
+                          const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                          float* scores, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!lse_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_score_lse: NULL lse_dev");
+    return score_entry(params, q_win, k, lse_dev, cu_seqlens_dev, seqlens_host, n_items, scores, workspace,
+                       workspace_bytes, stream);
 }
 
 int32_t audiokv_allocate(const audiokv_params* params, const float* weights_dev, int32_t n_segments,
@@ -383,11 +402,13 @@ int32_t audiokv_compact(const audiokv_params* params, const void* k, const void*
     return AUDIOKV_OK;
 }
 
-int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const void* k, const void* v,
-                      const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
-                      const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
-                      void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev, int32_t* cu_budgets_dev,
-                      void* workspace, size_t workspace_bytes, void* stream)
+namespace {
+int32_t evict_entry(const audiokv_params* params, const void* q_win, const void* k, const void* v,
+                    const float* lse_dev,
+                    const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
+                    const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
+                    void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev, int32_t* cu_budgets_dev,
+                    void* workspace, size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 1));
     Batch b;
@@ -441,7 +462,7 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
     }
     AUDIOKV_MARK(1);
     AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
-                             prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr), "score kernels");
+                             prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev), "score kernels");
     AUDIOKV_MARK(2);
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");
@@ -456,6 +477,31 @@ int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const voi
 #undef AUDIOKV_MARK
     if (prof) g_prof.recorded = true;
     return AUDIOKV_OK;
+}
+}  // namespace
+
+int32_t audiokv_evict(const audiokv_params* params, const void* q_win, const void* k, const void* v,
+                      const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
+                      const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
+                      void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev, int32_t* cu_budgets_dev,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    return evict_entry(params, q_win, k, v, nullptr, weights_dev, alloc_scope, cu_seqlens_dev, seqlens_host, n_items,
+                       ratio, cutoff_frac, alpha, k_out, v_out, indices_dev, budgets_dev, cu_budgets_dev, workspace,
+                       workspace_bytes, stream);
+}
+
+int32_t audiokv_evict_lse(const audiokv_params* params, const void* q_win, const void* k, const void* v,
+                          const float* lse_dev,
+                          const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
+                          const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
+                          void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev,
+                          int32_t* cu_budgets_dev, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!lse_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_evict_lse: NULL lse_dev");
+    return evict_entry(params, q_win, k, v, lse_dev, weights_dev, alloc_scope, cu_seqlens_dev, seqlens_host, n_items,
+                       ratio, cutoff_frac, alpha, k_out, v_out, indices_dev, budgets_dev, cu_budgets_dev, workspace,
+                       workspace_bytes, stream);
 }
 
 int32_t audiokv_decode_workspace_bytes(const audiokv_params* params, int32_t n_items, int64_t total_rows,

@@ -43,9 +43,10 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D);
 int score_padded_rows(int rows, int D);
 
 // between_sweeps: optional event recorded on `s` after the first sweep (timing aid), or nullptr.
+// lse: optional fp32 [items][H_q][W] natural-log softmax denominators of the window rows; given, sweep 1 is skipped.
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         int max_L, float* stats_ws, float* raw_out, hipStream_t s,
-                        hipEvent_t between_sweeps = nullptr);
+                        hipEvent_t between_sweeps = nullptr, const float* lse = nullptr);
 hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
                        float* pooled, hipStream_t s);
 

@@ -56,16 +56,17 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
 }
 
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
-                        int max_L, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps)
+                        int max_L, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
+                        const float* lse)
 {
     Plan p;
     const int rows = g.G * g.W;
     if (!make_plan(rows, g.D, &p)) return hipErrorInvalidValue;
     const int nsplit = score_num_splits(g.n_items * g.H_kv, max_L, rows, g.D);
     switch (g.D) {
-        case 64:  return launch_score_d64(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps);
-        case 128: return launch_score_d128(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps);
-        case 256: return launch_score_d256(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps);
+        case 64:  return launch_score_d64(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
+        case 128: return launch_score_d128(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
+        case 256: return launch_score_d256(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
     }
     return hipErrorInvalidValue;
 }

@@ -4,14 +4,14 @@
 namespace audiokv {
 
 hipError_t launch_score_d256(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between)
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between, const float* lse)
 {
     using namespace score_detail;
-    if (NB == 1 && WR == 1) return launch_both_sweeps<256, 1, 1>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 1 && WR == 2) return launch_both_sweeps<256, 1, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 1 && WR == 4) return launch_both_sweeps<256, 1, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 1 && WR == 7) return launch_both_sweeps<256, 1, 7>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
-    if (NB == 1 && WR == 8) return launch_both_sweeps<256, 1, 8>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between);
+    if (NB == 1 && WR == 1) return launch_both_sweeps<256, 1, 1>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between, lse);
+    if (NB == 1 && WR == 2) return launch_both_sweeps<256, 1, 2>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between, lse);
+    if (NB == 1 && WR == 4) return launch_both_sweeps<256, 1, 4>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between, lse);
+    if (NB == 1 && WR == 7) return launch_both_sweeps<256, 1, 7>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between, lse);
+    if (NB == 1 && WR == 8) return launch_both_sweeps<256, 1, 8>(g, q_win, k, cu_seq, nsplit, stats, raw, s, between, lse);
     return hipErrorInvalidValue;
 }
 

@@ -476,9 +476,28 @@ static __global__ __launch_bounds__(64) void score_merge_kernel(const float* __r
     cst[(size_t)head * rows_pad + r] = out;
 }
 
+// Row constants from log-sum-exp values that the caller already has (natural log of the softmax denominator of
+// every window row, as an attention kernel that ran the window's queries returns them): replaces sweep 1.
+static __global__ __launch_bounds__(64) void score_cst_from_lse_kernel(Geom g, const float* __restrict__ lse,
+                                                                       int rows_pad, float* __restrict__ cst)
+{
+    const int blocks_per_head = (rows_pad + 63) / 64;
+    const int head = blockIdx.x / blocks_per_head;
+    const int r = (blockIdx.x - head * blocks_per_head) * 64 + threadIdx.x;
+    if (r >= rows_pad) return;
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    float out = INFINITY;
+    if (r < g.G * g.W) {
+        const int qh = r / g.W, wrow = r - qh * g.W;
+        out = lse[((size_t)item * g.H_q + (size_t)h * g.G + qh) * g.W + wrow] * 1.44269504088896340736f;
+    }
+    cst[(size_t)head * rows_pad + r] = out;
+}
+
 template <int D, int NB, int WR>
 hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seq,
-                              int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between)
+                              int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+                              const float* lse)
 {
     using T = Tile<D, NB, WR>;
     const int n_heads = g.n_items * g.H_kv;
@@ -494,10 +513,15 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
-                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, (const float*)nullptr, raw);
-    hipLaunchKernelGGL(score_merge_kernel, dim3((unsigned)(n_heads * ((T::ROWS + 63) / 64))), dim3(64), 0, s,
-                       (const float*)stats, nsplit, T::ROWS, g.G * g.W, cst);
+    const unsigned merge_blocks = (unsigned)(n_heads * ((T::ROWS + 63) / 64));
+    if (lse) {
+        hipLaunchKernelGGL(score_cst_from_lse_kernel, dim3(merge_blocks), dim3(64), 0, s, g, lse, T::ROWS, cst);
+    } else {
+        hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
+                           (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, (const float*)nullptr, raw);
+        hipLaunchKernelGGL(score_merge_kernel, dim3(merge_blocks), dim3(64), 0, s, (const float*)stats, nsplit,
+                           T::ROWS, g.G * g.W, cst);
+    }
     if (between) {
         const hipError_t e = hipEventRecord(between, s);
         if (e != hipSuccess) return e;
@@ -511,10 +535,13 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
 
 // one translation unit per head_dim keeps the build parallel
 hipError_t launch_score_d64(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+        const float* lse);
 hipError_t launch_score_d128(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+        const float* lse);
 hipError_t launch_score_d256(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between);
+        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+        const float* lse);
 
 }  // namespace audiokv
