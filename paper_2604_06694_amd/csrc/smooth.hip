@@ -456,49 +456,197 @@ __device__ __forceinline__ cf chirp(int n, int L) {
 // exp(-2*pi*i*e/M) for 0 <= e < M/2 from the two tables of root M
 __device__ __forceinline__ cf tw_m(const cf* lo, const cf* hi, int e) { return cmul(hi[e >> 7], lo[e & (kTwLo - 1)]); }
 
-// In-place FFT of `x` (global, M = 2^logM complex). Forward: decimation in frequency, natural order in,
-// bit-reversed out. Inverse: decimation in time with conjugate twiddles, bit-reversed in, natural out,
-// unnormalised. `z` is a padded LDS scratch for min(M, 16384) complex; lo/hi are the twiddle tables of root M.
-__device__ __noinline__ void fft_pass(cf* __restrict__ x, int logM, bool inverse, cf* z, const cf* lo, const cf* hi) {
+// The transforms of size M = 2^logM on global memory are decimation in frequency forwards (natural order in,
+// bit-reversed out) and decimation in time backwards (bit-reversed in, natural out, conjugate twiddles,
+// unnormalised). The stages whose span fits a chunk of C = min(M, 16384) points run in LDS on one chunk at a time;
+// the one or two wider stages ("top" stages) run on global memory, fused into a single radix-4 pass when there are
+// two. `z` is the padded LDS chunk; lo/hi are the twiddle tables of root M.
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ cf mul_neg_i(cf a) { return {a.im, -a.re}; }
+__device__ __forceinline__ cf mul_pos_i(cf a) { return {-a.im, a.re}; }
+
+// two consecutive complex values as one 16-byte access (i even: the arrays are 16-byte aligned)
+__device__ __forceinline__ void ld2(const cf* x, int i, cf& a, cf& b) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(x + i);
+    a = {v[0], v[1]};
+    b = {v[2], v[3]};
+}
+__device__ __forceinline__ void st2(cf* x, int i, cf a, cf b) {
+    const f32x4 v = {a.re, a.im, b.re, b.im};
+    *reinterpret_cast<f32x4*>(x + i) = v;
+}
+
+__device__ __noinline__ void top_stages(cf* __restrict__ x, int logM, bool inverse, const cf* lo, const cf* hi) {
     const int tid = threadIdx.x;
+    const int M = 1 << logM;
+    const int extra = logM - (logM < kChunkLog ? logM : kChunkLog);
+    if (extra == 1) {
+        // one stage of half-size M/2: pairs (i, i + M/2), twiddle root^i
+        const int m = M >> 1;
+        for (int i = 2 * tid; i < m; i += 2 * kFftThreads) {
+            cf a[2], c[2];
+            ld2(x, i, a[0], a[1]);
+            ld2(x, i + m, c[0], c[1]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const cf w = tw_m(lo, hi, i + u);
+                if (!inverse) { const cf d = csub(a[u], c[u]); a[u] = cadd(a[u], c[u]); c[u] = cmul(d, w); }
+                else { const cf cw = cmul(c[u], cconj(w)); c[u] = csub(a[u], cw); a[u] = cadd(a[u], cw); }
+            }
+            st2(x, i, a[0], a[1]);
+            st2(x, i + m, c[0], c[1]);
+        }
+        __syncthreads();
+    } else if (extra == 2) {
+        // half-sizes M/2 and M/4 in one pass over the quadruples (i, i + M/4, i + M/2, i + 3M/4)
+        const int q = M >> 2;
+        for (int i = 2 * tid; i < q; i += 2 * kFftThreads) {
+            cf v[4][2];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ld2(x, i + r * q, v[r][0], v[r][1]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const cf w1 = tw_m(lo, hi, i + u);            // stage M/2 at offset i (offset i + M/4: times -i)
+                const cf w2 = tw_m(lo, hi, 2 * (i + u));      // stage M/4 at offset i
+                cf a0 = v[0][u], a1 = v[1][u], a2 = v[2][u], a3 = v[3][u];
+                if (!inverse) {
+                    const cf b0 = cadd(a0, a2), b2 = cmul(csub(a0, a2), w1);
+                    const cf b1 = cadd(a1, a3), b3 = mul_neg_i(cmul(csub(a1, a3), w1));
+                    a0 = cadd(b0, b1); a1 = cmul(csub(b0, b1), w2);
+                    a2 = cadd(b2, b3); a3 = cmul(csub(b2, b3), w2);
+                } else {
+                    const cf w1c = cconj(w1), w2c = cconj(w2);
+                    const cf t1 = cmul(a1, w2c), t3 = cmul(a3, w2c);
+                    const cf b0 = cadd(a0, t1), b1 = csub(a0, t1), b2 = cadd(a2, t3), b3 = csub(a2, t3);
+                    const cf u2 = cmul(b2, w1c), u3 = mul_pos_i(cmul(b3, w1c));
+                    a0 = cadd(b0, u2); a2 = csub(b0, u2);
+                    a1 = cadd(b1, u3); a3 = csub(b1, u3);
+                }
+                v[0][u] = a0; v[1][u] = a1; v[2][u] = a2; v[3][u] = a3;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) st2(x, i + r * q, v[r][0], v[r][1]);
+        }
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ void chunk_load(cf* z, const cf* __restrict__ x, int C) {
+    for (int i = 2 * threadIdx.x; i < C; i += 2 * kFftThreads) {
+        cf a, b;
+        ld2(x, i, a, b);
+        z[pad(i)] = a;
+        z[pad(i + 1)] = b;
+    }
+    __syncthreads();
+}
+__device__ __forceinline__ void chunk_store(cf* __restrict__ x, const cf* z, int C) {
+    for (int i = 2 * threadIdx.x; i < C; i += 2 * kFftThreads) st2(x, i, z[pad(i)], z[pad(i + 1)]);
+    __syncthreads();
+}
+
+// forward transform only (the filter's spectrum)
+__device__ __noinline__ void fft_forward(cf* __restrict__ x, int logM, cf* z, const cf* lo, const cf* hi) {
     const int M = 1 << logM;
     const int logC = logM < kChunkLog ? logM : kChunkLog;
     const int C = 1 << logC;
-    auto global_stage = [&](int s) {
-        const int m = 1 << s;
-        for (int b = tid; b < (M >> 1); b += kFftThreads) {
-            const int j = b & (m - 1);
-            const int i = ((b >> s) << (s + 1)) | j;
-            const cf w = tw_m(lo, hi, j << (logM - 1 - s));
-            const cf a = x[i], c = x[i + m];
-            if (!inverse) { x[i] = cadd(a, c); x[i + m] = cmul(csub(a, c), w); }
-            else { const cf cw = cmul(c, cconj(w)); x[i] = cadd(a, cw); x[i + m] = csub(a, cw); }
+    top_stages(x, logM, false, lo, hi);
+    for (int base = 0; base < M; base += C) {
+        chunk_load(z, x + base, C);
+        // stage s of the whole transform, restricted to a chunk, is stage s of a C-point transform with the
+        // twiddles of root M
+        fft_lds(z, logC, logM - 1, false, lo, hi);
+        chunk_store(x + base, z, C);
+    }
+}
+
+// x <- IFFT(FFT(x) * bhat), unnormalised: circular convolution with the filter whose spectrum is bhat (same
+// bit-reversed order). The product and both sets of chunk-local stages happen while a chunk sits in LDS.
+__device__ __noinline__ void convolve(cf* __restrict__ x, const cf* __restrict__ bhat, int logM, cf* z,
+                                      const cf* lo, const cf* hi) {
+    const int M = 1 << logM;
+    const int logC = logM < kChunkLog ? logM : kChunkLog;
+    const int C = 1 << logC;
+    top_stages(x, logM, false, lo, hi);
+    for (int base = 0; base < M; base += C) {
+        chunk_load(z, x + base, C);
+        fft_lds(z, logC, logM - 1, false, lo, hi);
+        for (int i = 2 * threadIdx.x; i < C; i += 2 * kFftThreads) {
+            cf b0, b1;
+            ld2(bhat + base, i, b0, b1);
+            z[pad(i)] = cmul(z[pad(i)], b0);
+            z[pad(i + 1)] = cmul(z[pad(i + 1)], b1);
         }
         __syncthreads();
-    };
-    auto chunk_stages = [&]() {
-        for (int base = 0; base < M; base += C) {
-            for (int i = tid; i < C; i += kFftThreads) z[pad(i)] = x[base + i];
-            __syncthreads();
-            // stage s of the whole transform, restricted to a chunk, is stage s of a C-point transform with the
-            // twiddles of root M
-            fft_lds(z, logC, logM - 1, inverse, lo, hi);
-            for (int i = tid; i < C; i += kFftThreads) x[base + i] = z[pad(i)];
-            __syncthreads();
-        }
-    };
-    if (!inverse) {
-        for (int s = logM - 1; s >= logC; --s) global_stage(s);
-        chunk_stages();
-    } else {
-        chunk_stages();
-        for (int s = logC; s < logM; ++s) global_stage(s);
+        fft_lds(z, logC, logM - 1, true, lo, hi);
+        chunk_store(x + base, z, C);
     }
+    top_stages(x, logM, true, lo, hi);
+}
+
+// workspace of the chirp-z path, in complex elements: per head one array of M; per item the filter spectrum (M)
+// and the chirp itself (L <= M / 2 entries in a slot of M, which keeps every array 16-byte aligned)
+struct BluesteinWs {
+    cf* base;
+    size_t M;          // stride unit: the largest transform of the batch
+    int n_heads;
+    __device__ cf* a_of(int head) const { return base + (size_t)head * M; }
+    __device__ cf* bhat_of(int item) const { return base + (size_t)n_heads * M + (size_t)item * (2 * M); }
+    __device__ cf* chirp_of(int item) const { return bhat_of(item) + M; }
+};
+
+// the first item with the same length computes (and owns) the filter spectrum and the chirp table
+__device__ __forceinline__ int owner_item(const int32_t* __restrict__ cu_seq, int item, int L) {
+    for (int i = 0; i < item; ++i)
+        if (cu_seq[i + 1] - cu_seq[i] == L) return i;
+    return item;
+}
+
+__device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
+    for (int t = threadIdx.x; t < kTwLo + n_hi; t += kFftThreads) {
+        const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
+        double sn, cs;
+        sincospi(2.0 * (double)e / (double)M, &sn, &cs);
+        const cf w = {(float)cs, (float)(-sn)};
+        if (t < kTwLo) lo[t] = w; else hi[t - kTwLo] = w;
+    }
+}
+
+// once per distinct length: chirp table and spectrum of the wrapped conjugate chirp
+__global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const int32_t* __restrict__ cu_seq, BluesteinWs ws)
+{
+    extern __shared__ float smem[];
+    const int item = blockIdx.x;
+    const int L = cu_seq[item + 1] - cu_seq[item];
+    if (pow2_length(L) || owner_item(cu_seq, item, L) != item) return;
+    const int tid = threadIdx.x;
+    const int logM = bluestein_log(L);
+    const int M = 1 << logM;
+    const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
+    cf* z = reinterpret_cast<cf*>(smem);
+    cf* lo = z + padded_len(C);
+    cf* hi = lo + kTwLo;
+    fill_tables(lo, hi, (M >> 8) + 1, M);
+    cf* B = ws.bhat_of(item);
+    cf* ch = ws.chirp_of(item);
+    for (int n = tid; n < L; n += kFftThreads) ch[n] = chirp(n, L);
+    __syncthreads();
+    // the convolution kernel conj(chirp), wrapped around M
+    for (int n = tid; n < M; n += kFftThreads) {
+        cf b = {0.f, 0.f};
+        if (n < L) b = cconj(ch[n]);
+        else if (n > M - L) b = cconj(ch[M - n]);
+        B[n] = b;
+    }
+    __syncthreads();
+    fft_forward(B, logM, z, lo, hi);
 }
 
 __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
-    double cutoff_frac, float alpha, float* __restrict__ out, cf* __restrict__ ws, size_t ws_stride,
+    double cutoff_frac, float alpha, float* __restrict__ out, BluesteinWs ws,
     int32_t* __restrict__ kstar_out, int cutoffs_only)
 {
     extern __shared__ float smem[];
@@ -523,36 +671,24 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     cf* lo = z + padded_len(C);
     cf* hi = lo + kTwLo;
     const int n_hi = (M >> 8) + 1;                    // exponents below M/2
-    cf* A = ws + (size_t)head * ws_stride;
-    cf* B = A + M;
+    const int owner = owner_item(cu_seq, item, L);
+    cf* A = ws.a_of(head);
+    const cf* Bhat = ws.bhat_of(owner);
+    const cf* ch = ws.chirp_of(owner);               // exp(-i*pi*n^2/L), n < L
 
-    for (int t = tid; t < kTwLo + n_hi; t += kFftThreads) {
-        const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
-        double sn, cs;
-        sincospi(2.0 * (double)e / (double)M, &sn, &cs);
-        const cf w = {(float)cs, (float)(-sn)};
-        if (t < kTwLo) lo[t] = w; else hi[t - kTwLo] = w;
-    }
-    // the convolution kernel conj(chirp), wrapped around M, and the chirped input
+    fill_tables(lo, hi, n_hi, M);
+    // the chirped input, zero beyond L
     for (int n = tid; n < M; n += kFftThreads) {
-        cf b = {0.f, 0.f}, a = {0.f, 0.f};
+        cf a = {0.f, 0.f};
         if (n < L) {
-            const cf w = chirp(n, L);
-            b = cconj(w);
+            const cf w = ch[n];
             const float sv = pool_on_load ? pooled_at(src, L, n, g.pool_kernel, g.pool_mode) : src[n];
             a = {sv * w.re, sv * w.im};
-        } else if (n > M - L) {
-            b = cconj(chirp(M - n, L));
         }
-        B[n] = b;
         A[n] = a;
     }
     __syncthreads();
-    fft_pass(B, logM, false, z, lo, hi);
-    fft_pass(A, logM, false, z, lo, hi);
-    for (int n = tid; n < M; n += kFftThreads) A[n] = cmul(A[n], B[n]);
-    __syncthreads();
-    fft_pass(A, logM, true, z, lo, hi);
+    convolve(A, Bhat, logM, z, lo, hi);
 
     // F_k = chirp(k) * A[k] / M; low-pass mask on the two-sided bin index (Eq. 17-18); the inverse transform is
     // the conjugate of a forward transform of conj(F~), so feed conj(F~) * chirp into the same machinery
@@ -576,7 +712,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
             const int bin = k < L - k ? k : L - k;
             const float wgt = mask_weight(bin, kstar, T);
             if (wgt > 0.f) {
-                const cf w = chirp(k, L);
+                const cf w = ch[k];
                 cf F = cmul(w, A[k]);
                 F = {F.re * inv_m * wgt, F.im * inv_m * wgt};
                 v = cmul(cconj(F), w);
@@ -585,15 +721,12 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
         A[k] = v;
     }
     __syncthreads();
-    fft_pass(A, logM, false, z, lo, hi);
-    for (int n = tid; n < M; n += kFftThreads) A[n] = cmul(A[n], B[n]);
-    __syncthreads();
-    fft_pass(A, logM, true, z, lo, hi);
+    convolve(A, Bhat, logM, z, lo, hi);
 
     // s~_n = Re(chirp(n) * A[n]) / (M * L); residual mix (Eq. 20)
     const float scale = inv_m / (float)L;
     for (int n = tid; n < L; n += kFftThreads) {
-        const cf y = cmul(chirp(n, L), A[n]);
+        const cf y = cmul(ch[n], A[n]);
         const float st = y.re * scale;
         if (alpha == 1.f) dst[n] = st;
         else {
@@ -621,7 +754,9 @@ size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv
     for (int i = 0; i < n_items; ++i)
         if (!pow2_length(seqlens_host[i])) max_log = max(max_log, bluestein_log(seqlens_host[i]));
     if (max_log == 0) return 0;
-    return (size_t)n_items * H_kv * 2 * ((size_t)1 << max_log) * sizeof(cf);
+    const size_t M = (size_t)1 << max_log;
+    // per head the working array (M), per item the filter spectrum (M) and the chirp table (a slot of M)
+    return ((size_t)n_items * H_kv * M + (size_t)n_items * 2 * M) * sizeof(cf);
 }
 
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
@@ -643,6 +778,9 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_bluestein_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(bluestein_prepare_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -658,9 +796,11 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         const size_t M = (size_t)1 << max_log;
         const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
         const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
+        const BluesteinWs bw{static_cast<cf*>(workspace), M, n_heads};
+        hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), smem, s, cu_seqlens, bw);
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
-                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out,
-                           static_cast<cf*>(workspace), 2 * M, kstar_out, cutoffs_only ? 1 : 0);
+                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
+                           cutoffs_only ? 1 : 0);
     }
     return hipGetLastError();
 }
