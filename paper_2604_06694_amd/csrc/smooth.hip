@@ -14,8 +14,10 @@
 // root of unity.
 //
 // Any other length (the transform length must be exactly L: zero-padding would be a different circular
-// filter) goes through Bluestein's chirp-z identity: a length-L DFT is a circular convolution with a chirp,
-// done with power-of-two FFTs of size M >= 2L - 1 in a per-head global-memory workspace. Stages whose span
+// filter) goes through Bluestein's chirp-z identity: a length-L DFT is a convolution with a chirp, done with
+// power-of-two FFTs in a per-head global-memory workspace. Only the K = k* + T + 1 lowest bins are ever needed
+// (everything above is masked), so the convolutions have L + K - 1 significant points and the transform size is
+// M >= L + K - 1 rather than 2L - 1: half the size for most lengths at the usual cutoffs. Stages whose span
 // exceeds the LDS (M > 16384) run on global memory, the rest on 16384-point chunks inside LDS.
 #include "common.h"
 
@@ -439,10 +441,20 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
 constexpr int kChunkLog = 14;                     // 16384 complex = 128 KiB: the part of an FFT that fits in LDS
 constexpr int kMaxBluesteinLog = 16;              // M <= 65536, i.e. L <= 32768
 
-__host__ __device__ inline int bluestein_log(int L) {     // smallest power of two >= 2L - 1
+// log2 of the transform size for L samples and K wanted bins: the smallest power of two >= L + K - 1
+__host__ __device__ inline int bluestein_log(int L, int K) {
     int lg = 1;
-    while ((1 << lg) < 2 * L - 1) ++lg;
+    while ((1 << lg) < L + K - 1) ++lg;
     return lg;
+}
+__host__ __device__ inline int bluestein_log_max(int L) { return bluestein_log(L, (L >> 1) + 1); }
+
+// bins 0 .. K-1 that the filter can leave non-zero (all of them when the cutoff is found from the spectrum)
+__host__ __device__ inline int wanted_bins(int L, double cutoff_frac, int cutoff_mode, int taper_bins) {
+    const int half = L >> 1;
+    if (cutoff_mode != AUDIOKV_CUTOFF_FRACTION) return half + 1;
+    const long long ktop = (long long)floor(cutoff_frac * (double)half) + taper_bins;
+    return (int)(ktop < half ? ktop : half) + 1;
 }
 
 // exp(-i*pi*n^2/L): the chirp, from an exactly reduced angle in float64
@@ -586,15 +598,15 @@ __device__ __noinline__ void convolve(cf* __restrict__ x, const cf* __restrict__
     top_stages(x, logM, true, lo, hi);
 }
 
-// workspace of the chirp-z path, in complex elements: per head one array of M; per item the filter spectrum (M)
-// and the chirp itself (L <= M / 2 entries in a slot of M, which keeps every array 16-byte aligned)
+// workspace of the chirp-z path, in complex elements: per head one array of M; per item the spectra of the two
+// filters (M each) and the chirp itself (L <= M entries in a slot of M, which keeps every array 16-byte aligned)
 struct BluesteinWs {
     cf* base;
     size_t M;          // stride unit: the largest transform of the batch
     int n_heads;
     __device__ cf* a_of(int head) const { return base + (size_t)head * M; }
-    __device__ cf* bhat_of(int item) const { return base + (size_t)n_heads * M + (size_t)item * (2 * M); }
-    __device__ cf* chirp_of(int item) const { return bhat_of(item) + M; }
+    __device__ cf* bhat_of(int item, int which) const { return base + (size_t)n_heads * M + ((size_t)item * 3 + which) * M; }
+    __device__ cf* chirp_of(int item) const { return bhat_of(item, 2); }
 };
 
 // the first item with the same length computes (and owns) the filter spectrum and the chirp table
@@ -614,34 +626,46 @@ __device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
     }
 }
 
-// once per distinct length: chirp table and spectrum of the wrapped conjugate chirp
-__global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const int32_t* __restrict__ cu_seq, BluesteinWs ws)
+// once per distinct length: the chirp table and the spectra of the two convolution filters.
+//   forward transform (L samples in, K bins out): conj(chirp(m)) for m in (-L, K), wrapped around M;
+//   inverse transform (K bins in, L samples out): conj(chirp(m)) for m in (-K, L), which is the first one read
+//   backwards, so its spectrum is the first spectrum at the negated frequency.
+__global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const int32_t* __restrict__ cu_seq, BluesteinWs ws,
+                                                                         double cutoff_frac, int cutoff_mode, int taper_bins)
 {
     extern __shared__ float smem[];
     const int item = blockIdx.x;
     const int L = cu_seq[item + 1] - cu_seq[item];
     if (pow2_length(L) || owner_item(cu_seq, item, L) != item) return;
     const int tid = threadIdx.x;
-    const int logM = bluestein_log(L);
+    const int K = wanted_bins(L, cutoff_frac, cutoff_mode, taper_bins);
+    const int logM = bluestein_log(L, K);
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
     cf* z = reinterpret_cast<cf*>(smem);
     cf* lo = z + padded_len(C);
     cf* hi = lo + kTwLo;
     fill_tables(lo, hi, (M >> 8) + 1, M);
-    cf* B = ws.bhat_of(item);
+    cf* B1 = ws.bhat_of(item, 0);
+    cf* B2 = ws.bhat_of(item, 1);
     cf* ch = ws.chirp_of(item);
     for (int n = tid; n < L; n += kFftThreads) ch[n] = chirp(n, L);
     __syncthreads();
-    // the convolution kernel conj(chirp), wrapped around M
     for (int n = tid; n < M; n += kFftThreads) {
         cf b = {0.f, 0.f};
-        if (n < L) b = cconj(ch[n]);
+        if (n < K) b = cconj(ch[n]);
         else if (n > M - L) b = cconj(ch[M - n]);
-        B[n] = b;
+        B1[n] = b;
     }
     __syncthreads();
-    fft_forward(B, logM, z, lo, hi);
+    fft_forward(B1, logM, z, lo, hi);
+    // both spectra sit in bit-reversed order: slot p holds frequency brev(p)
+    const int shift = 32 - logM;
+    for (int p = tid; p < M; p += kFftThreads) {
+        const unsigned f = __brev((unsigned)p) >> shift;
+        const unsigned nf = (M - f) & (M - 1);
+        B2[p] = B1[__brev(nf) >> shift];
+    }
 }
 
 __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
@@ -664,7 +688,8 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
         if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
         return;
     }
-    const int logM = bluestein_log(L);
+    const int K = wanted_bins(L, cutoff_frac, g.cutoff_mode, T);
+    const int logM = bluestein_log(L, K);
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
     cf* z = reinterpret_cast<cf*>(smem);
@@ -673,7 +698,6 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const int n_hi = (M >> 8) + 1;                    // exponents below M/2
     const int owner = owner_item(cu_seq, item, L);
     cf* A = ws.a_of(head);
-    const cf* Bhat = ws.bhat_of(owner);
     const cf* ch = ws.chirp_of(owner);               // exp(-i*pi*n^2/L), n < L
 
     fill_tables(lo, hi, n_hi, M);
@@ -688,10 +712,12 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
         A[n] = a;
     }
     __syncthreads();
-    convolve(A, Bhat, logM, z, lo, hi);
+    convolve(A, ws.bhat_of(owner, 0), logM, z, lo, hi);
 
-    // F_k = chirp(k) * A[k] / M; low-pass mask on the two-sided bin index (Eq. 17-18); the inverse transform is
-    // the conjugate of a forward transform of conj(F~), so feed conj(F~) * chirp into the same machinery
+    // F_k = chirp(k) * A[k] / M for k < K. Low-pass mask (Eq. 17-18), then the inverse real transform from the
+    // one-sided bins: s~_n = (1/L) Re sum_{k<K} g_k F~_k e^{+2 pi i k n / L}, g_k = 1 for k = 0 and for the Nyquist
+    // bin of an even L, else 2. That sum is the conjugate of a forward chirp-z transform of conj(g F~), K points
+    // in and L points out, so conj(g F~) * chirp goes into the same machinery with the second filter.
     int kstar = (int)floor(cutoff_frac * (double)(L >> 1));
     const float inv_m = 1.0f / (float)M;
     if (g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION) {
@@ -708,9 +734,8 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     if (cutoffs_only) return;
     for (int k = tid; k < M; k += kFftThreads) {
         cf v = {0.f, 0.f};
-        if (k < L) {
-            const int bin = k < L - k ? k : L - k;
-            const float wgt = mask_weight(bin, kstar, T);
+        if (k < K) {
+            const float wgt = mask_weight(k, kstar, T) * ((k == 0 || 2 * k == L) ? 1.f : 2.f);
             if (wgt > 0.f) {
                 const cf w = ch[k];
                 cf F = cmul(w, A[k]);
@@ -721,7 +746,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
         A[k] = v;
     }
     __syncthreads();
-    convolve(A, Bhat, logM, z, lo, hi);
+    convolve(A, ws.bhat_of(owner, 1), logM, z, lo, hi);
 
     // s~_n = Re(chirp(n) * A[n]) / (M * L); residual mix (Eq. 20)
     const float scale = inv_m / (float)L;
@@ -747,16 +772,17 @@ hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlen
     return hipGetLastError();
 }
 
-bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && bluestein_log(L) <= kMaxBluesteinLog); }
+bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && bluestein_log_max(L) <= kMaxBluesteinLog); }
 
 size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
+    // sized for the largest transform any cutoff can ask for (all bins wanted)
     int max_log = 0;
     for (int i = 0; i < n_items; ++i)
-        if (!pow2_length(seqlens_host[i])) max_log = max(max_log, bluestein_log(seqlens_host[i]));
+        if (!pow2_length(seqlens_host[i])) max_log = max(max_log, bluestein_log_max(seqlens_host[i]));
     if (max_log == 0) return 0;
     const size_t M = (size_t)1 << max_log;
-    // per head the working array (M), per item the filter spectrum (M) and the chirp table (a slot of M)
-    return ((size_t)n_items * H_kv * M + (size_t)n_items * 2 * M) * sizeof(cf);
+    // per head the working array (M), per item the two filter spectra and the chirp table (a slot of M each)
+    return ((size_t)n_items * H_kv * M + (size_t)n_items * 3 * M) * sizeof(cf);
 }
 
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
@@ -768,7 +794,8 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
     int max_pow2 = 0, max_log = 0;
     for (int i = 0; i < n_items; ++i) {
         if (pow2_length(seqlens_host[i])) max_pow2 = max(max_pow2, seqlens_host[i]);
-        else max_log = max(max_log, bluestein_log(seqlens_host[i]));
+        else max_log = max(max_log, bluestein_log(seqlens_host[i], wanted_bins(seqlens_host[i], cutoff_frac, g.cutoff_mode,
+                                                                                g.taper_bins)));
     }
     const int n_heads = g.n_items * g.H_kv;
     static bool attr_set = false;
@@ -797,7 +824,8 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
         const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
         const BluesteinWs bw{static_cast<cf*>(workspace), M, n_heads};
-        hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), smem, s, cu_seqlens, bw);
+        hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), smem, s, cu_seqlens, bw,
+                           cutoff_frac, g.cutoff_mode, g.taper_bins);
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
                            cutoffs_only ? 1 : 0);
