@@ -785,31 +785,73 @@ size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv
     return ((size_t)n_items * H_kv * M + (size_t)n_items * 3 * M) * sizeof(cf);
 }
 
+namespace {
+struct SmoothPlan { int max_pow2 = 0, max_log = 0; };
+
+SmoothPlan plan_smooth(const Geom& g, const int32_t* seqlens_host, int n_items, double cutoff_frac) {
+    SmoothPlan p;
+    for (int i = 0; i < n_items; ++i) {
+        if (pow2_length(seqlens_host[i])) p.max_pow2 = max(p.max_pow2, seqlens_host[i]);
+        else p.max_log = max(p.max_log, bluestein_log(seqlens_host[i], wanted_bins(seqlens_host[i], cutoff_frac,
+                                                                                   g.cutoff_mode, g.taper_bins)));
+    }
+    return p;
+}
+
+hipError_t smooth_kernel_attributes() {
+    static bool attr_set = false;
+    if (attr_set) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_pow2_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_bluestein_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(bluestein_prepare_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) attr_set = true;
+    return e;
+}
+
+size_t bluestein_smem(const Geom& g, size_t M) {
+    const size_t extra = g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION ? sizeof(EnergyScratch) + 2 * sizeof(cf) : 0;
+    const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
+    return (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
+}
+}  // namespace
+
+bool smooth_needs_filters(const Geom& g, const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha) {
+    return alpha != 0.0 && plan_smooth(g, seqlens_host, n_items, cutoff_frac).max_log > 0;
+}
+
+hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const int32_t* seqlens_host, int n_items,
+                                 double cutoff_frac, void* workspace, hipStream_t s)
+{
+    const SmoothPlan pl = plan_smooth(g, seqlens_host, n_items, cutoff_frac);
+    if (pl.max_log == 0) return hipSuccess;
+    if (!workspace) return hipErrorInvalidValue;
+    hipError_t e = smooth_kernel_attributes();
+    if (e != hipSuccess) return e;
+    const size_t M = (size_t)1 << pl.max_log;
+    const BluesteinWs bw{static_cast<cf*>(workspace), M, g.n_items * g.H_kv};
+    hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), bluestein_smem(g, M), s, cu_seqlens,
+                       bw, cutoff_frac, g.cutoff_mode, g.taper_bins);
+    return hipGetLastError();
+}
+
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s)
+                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s,
+                         bool filters_ready)
 {
     if (cutoffs_only && !kstar_out) return hipErrorInvalidValue;
     const size_t extra = g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION ? sizeof(EnergyScratch) + 2 * sizeof(cf) : 0;
-    int max_pow2 = 0, max_log = 0;
-    for (int i = 0; i < n_items; ++i) {
-        if (pow2_length(seqlens_host[i])) max_pow2 = max(max_pow2, seqlens_host[i]);
-        else max_log = max(max_log, bluestein_log(seqlens_host[i], wanted_bins(seqlens_host[i], cutoff_frac, g.cutoff_mode,
-                                                                                g.taper_bins)));
-    }
+    const SmoothPlan pl = plan_smooth(g, seqlens_host, n_items, cutoff_frac);
+    const int max_pow2 = pl.max_pow2, max_log = pl.max_log;
     const int n_heads = g.n_items * g.H_kv;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_pow2_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_bluestein_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(bluestein_prepare_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    {
+        const hipError_t e = smooth_kernel_attributes();
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
     if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
@@ -820,13 +862,13 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
     }
     if (max_log > 0 && alpha != 0.0) {
         if (!workspace) return hipErrorInvalidValue;
+        if (!filters_ready) {
+            const hipError_t e = launch_smooth_filters(g, cu_seqlens, seqlens_host, n_items, cutoff_frac, workspace, s);
+            if (e != hipSuccess) return e;
+        }
         const size_t M = (size_t)1 << max_log;
-        const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
-        const size_t smem = (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
         const BluesteinWs bw{static_cast<cf*>(workspace), M, n_heads};
-        hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), smem, s, cu_seqlens, bw,
-                           cutoff_frac, g.cutoff_mode, g.taper_bins);
-        hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
+        hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), bluestein_smem(g, M), s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
                            cutoffs_only ? 1 : 0);
     }
