@@ -118,8 +118,18 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+_LENS_CACHE: dict = {}
+
+
 def _host_lens(seqlens: Sequence[int]):
-    arr = (C.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
+    """ctypes int32 array of the lengths; the arrays of recent length lists are kept (a serving loop passes the
+    same few lists over and over, and building the array costs more than the rest of the marshalling)."""
+    key = tuple(int(x) for x in seqlens)
+    arr = _LENS_CACHE.get(key)
+    if arr is None:
+        if len(_LENS_CACHE) > 256:
+            _LENS_CACHE.clear()
+        arr = _LENS_CACHE[key] = (C.c_int32 * len(key))(*key)
     return arr
 
 
@@ -148,18 +158,34 @@ def n_keep(ratio: float, L: int) -> int:
     return _lib.audiokv_n_keep(float(ratio), int(L))
 
 
+_SIZE_CACHE: dict = {}
+
+
+def _cached(key, compute):
+    v = _SIZE_CACHE.get(key)
+    if v is None:
+        if len(_SIZE_CACHE) > 1024:
+            _SIZE_CACHE.clear()
+        v = _SIZE_CACHE[key] = compute()
+    return v
+
+
 def total_kept(p: Params, seqlens: Sequence[int], ratio: float) -> int:
-    out = C.c_int64(0)
-    cp = p.c()
-    _check(_lib.audiokv_total_kept(C.byref(cp), len(seqlens), _host_lens(seqlens), float(ratio), C.byref(out)))
-    return out.value
+    def compute():
+        out = C.c_int64(0)
+        cp = p.c()
+        _check(_lib.audiokv_total_kept(C.byref(cp), len(seqlens), _host_lens(seqlens), float(ratio), C.byref(out)))
+        return out.value
+    return _cached(("rows", dataclasses.astuple(p), tuple(int(x) for x in seqlens), float(ratio)), compute)
 
 
 def workspace_bytes(p: Params, seqlens: Sequence[int]) -> int:
-    out = C.c_size_t(0)
-    cp = p.c()
-    _check(_lib.audiokv_workspace_bytes(C.byref(cp), len(seqlens), _host_lens(seqlens), C.byref(out)))
-    return out.value
+    def compute():
+        out = C.c_size_t(0)
+        cp = p.c()
+        _check(_lib.audiokv_workspace_bytes(C.byref(cp), len(seqlens), _host_lens(seqlens), C.byref(out)))
+        return out.value
+    return _cached(("ws", dataclasses.astuple(p), tuple(int(x) for x in seqlens)), compute)
 
 
 def _workspace(p: Params, seqlens: Sequence[int], device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
