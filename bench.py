@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--cutoff", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-layer", action="store_true", help="skip the one-launch-per-layer timing")
     ap.add_argument("--no-lse", action="store_true", help="skip the timing of the variant that is given the window's log-sum-exp")
     ap.add_argument("--no-decode", action="store_true", help="skip the timing of the decode-side consumer")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -234,7 +235,7 @@ def main():
     }
     # the same work as one launch per layer (28 calls, each layer its own budget pool): what a framework that evicts
     # layer by layer during prefill would issue; `value` above is the all-layers-batched call
-    if cfg.seqlen is not None and cfg.n_items > 1:
+    if cfg.seqlen is not None and cfg.n_items > 1 and not args.no_per_layer:
         L0 = lens[0]
         per_q = cfg.n_q_heads * cfg.window * cfg.head_dim
         per_kv = cfg.n_kv_heads * L0 * cfg.head_dim
