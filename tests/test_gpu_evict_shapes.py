@@ -78,3 +78,39 @@ def test_evict_shapes(A, H_q, H_kv, d, W, lens, layout, causal, ratio):
                 thr = np.sort(s_hat[:L - W])[::-1][want - 1]
                 assert np.all(np.abs(s_hat[diff] - thr) <= SCORE_RTOL * np.abs(s_hat).max())
     assert np.mean(agree) >= 0.999, agree
+
+
+@pytest.mark.parametrize("L,W,ratio", [(64, 64, 1.0), (128, 32, 0.25), (96, 16, 1.0), (33, 1, 0.5), (4096, 1, 0.01)])
+def test_evict_degenerate_budgets(A, L, W, ratio):
+    """Window as long as the sequence, budgets equal to the window (nothing but the forced tail is kept),
+    everything kept, a one-token window, one percent kept."""
+    rng = np.random.default_rng(L + W)
+    H_q, H_kv, d = 4, 2, 64
+    it = {"q_win": f64_to_bf16_bits(rng.standard_normal((H_q, W, d))),
+          "k": f64_to_bf16_bits(rng.standard_normal((H_kv, L, d))),
+          "v": f64_to_bf16_bits(rng.standard_normal((H_kv, L, d)))}
+    p = A.Params(H_q, H_kv, d, W)
+    w = np.array([0.3, 0.7], dtype=np.float32)
+    out = A.evict(p, bf16_tensor(it["q_win"].reshape(-1)), bf16_tensor(it["k"].reshape(-1)), bf16_tensor(it["v"].reshape(-1)),
+                  torch.from_numpy(w).cuda(), [L], ratio, 0.25, 1.0, alloc_scope=A.SCOPE_ITEM)
+    torch.cuda.synchronize()
+    b, cu = out["budgets"].cpu().numpy(), out["cu_budgets"].cpu().numpy()
+    ref_b, _ = O.allocate(w.astype(np.float64), L, ratio, window=W, floor_frac=float(np.float32(p.floor_frac)))
+    assert np.array_equal(b, ref_b) and b.sum() == O.n_keep_of(ratio, L) * H_kv
+    idx = out["indices"].cpu().numpy()
+    ko = bf16_bits(out["k_out"])
+    s = O.score(bf16_bits_to_f64(it["q_win"]), bf16_bits_to_f64(it["k"]))
+    for h in range(H_kv):
+        mine = idx[cu[h]:cu[h + 1]]
+        assert np.array_equal(mine[-W:], np.arange(L - W, L)) and np.all(np.diff(mine) > 0)
+        assert np.array_equal(ko[cu[h]:cu[h + 1]], it["k"][h][mine])
+        if b[h] == W:
+            assert np.array_equal(mine, np.arange(L - W, L))
+        if b[h] == L:
+            assert np.array_equal(mine, np.arange(L))
+        ref = O.select(O.smooth(s[h], 0.25, 1.0), int(b[h]), W)
+        diff = np.setxor1d(mine, ref)
+        if len(diff):
+            s_hat = O.smooth(s[h], 0.25, 1.0)
+            thr = np.sort(s_hat[:L - W])[::-1][int(b[h]) - W - 1]
+            assert np.all(np.abs(s_hat[diff] - thr) <= SCORE_RTOL * np.abs(s_hat).max())
