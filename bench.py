@@ -261,6 +261,35 @@ def main():
         res["one_launch_per_layer"] = {"ms_per_step": dt_layer * 1e3, "value": evicted / dt_layer,
                                        "note": "28 audiokv_evict calls of one layer each, per-layer budget pools; "
                                                "outputs of every layer written to the same buffers"}
+        # the same 28 calls issued round-robin on three streams (own workspace and output buffers per stream):
+        # the one-workgroup-per-head stages of one layer then overlap the score kernels of the next
+        n_str = 3
+        streams = [torch.cuda.Stream() for _ in range(n_str)]
+        slot_ws = [torch.empty_like(ws1) for _ in range(n_str)]
+        slot_out = [{key: torch.empty_like(val) for key, val in o1.items() if torch.is_tensor(val) and key != "workspace"}
+                    for _ in range(n_str)]
+
+        def layer_steps_streams():
+            for i in range(cfg.n_items):
+                j = i % n_str
+                with torch.cuda.stream(streams[j]):
+                    A.evict(p, q[i * per_q:(i + 1) * per_q], k[i * per_kv:(i + 1) * per_kv], v[i * per_kv:(i + 1) * per_kv],
+                            w[i * cfg.n_kv_heads:(i + 1) * cfg.n_kv_heads], [L0], cfg.ratio, cfg.cutoff, cfg.alpha,
+                            alloc_scope=A.SCOPE_ITEM, cu_seqlens=cu1, workspace=slot_ws[j], outputs=slot_out[j])
+        torch.cuda.synchronize()
+        layer_steps_streams()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_rep):
+            layer_steps_streams()
+        torch.cuda.synchronize()
+        dt_ls = (time.perf_counter() - t0) / n_rep
+        res["one_launch_per_layer"]["three_streams_ms_per_step"] = dt_ls * 1e3
+        res["one_launch_per_layer"]["three_streams_value"] = evicted / dt_ls
+        # the last layers of the one-stream run and of the three-stream run must agree bit for bit
+        last = (cfg.n_items - 1) % n_str
+        res["one_launch_per_layer"]["streams_match"] = bool(torch.equal(slot_out[last]["indices"], o1["indices"]))
+        del slot_ws, slot_out
         step()                                   # restore the batched outputs for what follows
         torch.cuda.synchronize()
     if not args.no_lse:
