@@ -23,5 +23,7 @@ _BINDING_NAMES = (
 def __getattr__(name):
     if name == "binding" or name in _BINDING_NAMES:
         b = importlib.import_module(".binding", __name__)
-        return b if name == "binding" else getattr(b, name)
+        value = b if name == "binding" else getattr(b, name)
+        globals()[name] = value          # later lookups find it without coming through here
+        return value
     raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -60,6 +60,10 @@ class Params:
     cutoff_mode: int = CUTOFF_FRACTION
     taper_bins: int = 0
 
+    def key(self) -> tuple:
+        return (self.n_q_heads, self.n_kv_heads, self.head_dim, self.window, self.pool_kernel, self.pool_mode,
+                self.causal, self.kv_layout, self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins)
+
     def c(self) -> _CParams:
         return _CParams(C.sizeof(_CParams), self.n_q_heads, self.n_kv_heads, self.head_dim, self.window,
                         self.pool_kernel, self.pool_mode, self.causal, self.kv_layout,
@@ -124,12 +128,12 @@ _LENS_CACHE: dict = {}
 def _host_lens(seqlens: Sequence[int]):
     """ctypes int32 array of the lengths; the arrays of recent length lists are kept (a serving loop passes the
     same few lists over and over, and building the array costs more than the rest of the marshalling)."""
-    key = tuple(int(x) for x in seqlens)
+    key = tuple(seqlens)
     arr = _LENS_CACHE.get(key)
     if arr is None:
         if len(_LENS_CACHE) > 256:
             _LENS_CACHE.clear()
-        arr = _LENS_CACHE[key] = (C.c_int32 * len(key))(*key)
+        arr = _LENS_CACHE[key] = (C.c_int32 * len(key))(*[int(x) for x in key])
     return arr
 
 
@@ -176,7 +180,7 @@ def total_kept(p: Params, seqlens: Sequence[int], ratio: float) -> int:
         cp = p.c()
         _check(_lib.audiokv_total_kept(C.byref(cp), len(seqlens), _host_lens(seqlens), float(ratio), C.byref(out)))
         return out.value
-    return _cached(("rows", dataclasses.astuple(p), tuple(int(x) for x in seqlens), float(ratio)), compute)
+    return _cached(("rows", p.key(), tuple(seqlens), float(ratio)), compute)
 
 
 def workspace_bytes(p: Params, seqlens: Sequence[int]) -> int:
@@ -185,7 +189,7 @@ def workspace_bytes(p: Params, seqlens: Sequence[int]) -> int:
         cp = p.c()
         _check(_lib.audiokv_workspace_bytes(C.byref(cp), len(seqlens), _host_lens(seqlens), C.byref(out)))
         return out.value
-    return _cached(("ws", dataclasses.astuple(p), tuple(int(x) for x in seqlens)), compute)
+    return _cached(("ws", p.key(), tuple(seqlens)), compute)
 
 
 def _workspace(p: Params, seqlens: Sequence[int], device, workspace: Optional[torch.Tensor]) -> torch.Tensor:

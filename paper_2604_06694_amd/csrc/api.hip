@@ -447,10 +447,12 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
     const bool prof = g_prof.enabled && g_prof.created;
     const bool side_filters = !prof && smooth_needs_filters(g, seqlens_host, n_items, cutoff_frac, alpha);
+    // a small pool is allocated faster than a fork and a join are issued: keep it in line then
+    const bool side = !prof && (side_filters || hps >= 32);
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
     AUDIOKV_MARK(0);
-    if (prof) {
-        // stage timing wants one kernel per interval: keep the allocation in line
+    if (!side) {
+        // (stage timing wants one kernel per interval: then, too, the allocation stays in line)
         AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
                                     budgets_dev, cu_budgets_dev, s), "allocate kernel");
     } else {
@@ -473,7 +475,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, ws + w.fft_off, nullptr, false, s, side_filters), "smooth kernel");
     AUDIOKV_MARK(3);
-    if (!prof && !side_filters) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
+    if (side && !side_filters) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
     AUDIOKV_MARK(4);
