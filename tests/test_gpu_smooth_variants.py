@@ -187,3 +187,47 @@ def test_cutoff_argument_validation(A):
     # a constant signal has no energy outside DC: the variant without DC settles on its first bin
     ks = A.smooth_cutoffs(A.Params(1, 1, 128, 1, cutoff_mode=A.CUTOFF_ENERGY_NO_DC), t, [64], 0.9).cpu().numpy()
     assert 1 <= ks[0] <= 32
+
+
+def test_alpha_zero_is_a_bitwise_copy_at_any_length(A):
+    rng = np.random.default_rng(31)
+    lens = [1000, 512, 37]
+    H = 2
+    flat = np.concatenate([score_like(rng, H, L).reshape(-1) for L in lens])
+    t = torch.from_numpy(flat).cuda()
+    for mode in (A.CUTOFF_FRACTION, A.CUTOFF_ENERGY):
+        out = A.smooth(A.Params(H, H, 128, 1, cutoff_mode=mode, taper_bins=2), t, lens, 0.5, 0.0)
+        assert torch.equal(out, t)
+
+
+def test_evict_energy_cutoff_on_ragged_lengths(A):
+    # lengths that are not powers of two, cutoff found from the spectrum: the filters are prepared beside the
+    # score kernels for all bins; fused must equal composed
+    rng = np.random.default_rng(32)
+    H_q, H_kv, d, W = 8, 2, 64, 16
+    lens = [700, 1024, 333]
+    from workloads import f64_to_bf16_bits
+    q = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_q, W, d))).reshape(-1) for _ in lens]))
+    k = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_kv, L, d))).reshape(-1) for L in lens]))
+    v = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_kv, L, d))).reshape(-1) for L in lens]))
+    w = torch.rand(len(lens) * H_kv, device="cuda") + 0.1
+    p = A.Params(H_q, H_kv, d, W, cutoff_mode=A.CUTOFF_ENERGY_NO_DC, taper_bins=3)
+    out = A.evict(p, q, k, v, w, lens, 0.5, 0.8, 1.0, alloc_scope=A.SCOPE_ITEM)
+    s = A.score(p, q, k, lens)
+    b, cu = A.allocate(p, w, len(lens), H_kv, lens, 0.5)
+    sh = A.smooth(p, s, lens, 0.8, 1.0)
+    idx = A.select(p, sh, b, cu, lens, out["total_rows"])
+    torch.cuda.synchronize()
+    assert torch.equal(b, out["budgets"])
+    assert torch.equal(idx, out["indices"][:out["total_rows"]])
+    # and the smoothed scores against the oracle with the kernel's own (checked) cutoffs
+    ks = A.smooth_cutoffs(p, s, lens, 0.8).cpu().numpy()
+    s_host, sh_host = s.cpu().numpy(), sh.cpu().numpy()
+    off = 0
+    for i, L in enumerate(lens):
+        for h in range(H_kv):
+            x = s_host[off:off + L].astype(np.float64)
+            check_kstar(O.rdft(x), 0.8, True, int(ks[i * H_kv + h]))
+            ref = O.smooth(x, 0.0, 1.0, k_star=int(ks[i * H_kv + h]), taper_bins=3)
+            assert rel_err(sh_host[off:off + L], ref) <= SCORE_RTOL
+            off += L
