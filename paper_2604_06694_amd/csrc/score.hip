@@ -41,7 +41,9 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
     // A head is cut into key ranges so that the grid fills the 256 CUs in whole rounds: pick the split
     // count that minimises rounds x (tiles per workgroup + fixed prologue cost, in tiles).
     const int tiles = (max_L + p.tile_keys - 1) / p.tile_keys;
-    const int slots = 256 * (p.WR >= 7 ? 1 : 2);      // resident workgroups
+    // resident workgroups: two per CU when a wave holds one row tile (128 registers, 59 KB of LDS) or the
+    // workgroup is small, one when the eight waves take all the registers
+    const int slots = 256 * ((p.NB == 1 && D <= 128) || p.WR < 7 ? 2 : 1);
     const int overhead = 3;
     int best = 1;
     long long best_cost = -1;

@@ -91,7 +91,7 @@ __device__ __forceinline__ int last_visible(const Geom& g, int L, int R, int r) 
 __device__ __forceinline__ constexpr int c_row(int i, int g2) { return (i >> 2) * 8 + g2 * 4 + (i & 3); }
 
 template <int D, int NB, int WR, bool SWEEP2>
-__global__ __launch_bounds__(64 * (WR + 1)) void score_kernel(
+__global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 1) void score_kernel(
     Geom g, const __bf16* __restrict__ q_win, const __bf16* __restrict__ k,
     const int32_t* __restrict__ cu_seq, int nsplit,
     float* __restrict__ stats,        // sweep 1 out: [head][split][ROWS][2] = (max in base-2 units, sum of exp2)
