@@ -1,5 +1,5 @@
-// Host-side planning for the score kernels: which (row blocks per wave, row-splitting
-// waves) instantiation covers G*W window rows, and into how many key ranges a head is cut.
+// Host-side planning for the score kernels: which (row blocks per wave, row-splitting waves) instantiation
+// covers G*W window rows in each of the two sweeps, and into how many key ranges a head is cut.
 #include "score_impl.h"
 
 namespace audiokv {
@@ -8,17 +8,21 @@ namespace {
 
 struct Plan { int NB, WR, rows_pad, tile_keys; };
 
-// Instantiated (32-row blocks per wave, waves per workgroup) pairs, by padded row count (must match score_d*.hip).
+// Instantiated (32-row blocks per wave, waves per workgroup) pairs in order of preference per sweep: the first
+// that holds the rows is taken (all must exist in score_d*.hip). The sweeps differ where their register needs do:
+// three row tiles per wave fit the registers of sweep 1 (and let two 4-wave workgroups share a CU at 256 rows),
+// but spill in sweep 2, which also carries the row constants.
 struct Combo { int NB, WR; };
-const Combo kCombos128[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {2, 4}, {2, 7}, {2, 8}};   // d = 64, 128
-const Combo kCombos256[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {1, 8}};                   // d = 256
+const Combo kSweep1_128[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {3, 3}, {2, 7}, {3, 6}};   // d = 64, 128
+const Combo kSweep2_128[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {2, 4}, {2, 7}, {2, 8}};
+const Combo kCombos256[] = {{1, 1}, {1, 2}, {1, 4}, {1, 7}, {1, 8}};                    // d = 256, both sweeps
 
-bool make_plan(int rows, int D, Plan* out) {
+bool make_plan(int rows, int D, int sweep, Plan* out) {
     const Combo* cs; int n;
-    if (D == 64 || D == 128) { cs = kCombos128; n = 7; }
+    if (D == 64 || D == 128) { cs = sweep == 1 ? kSweep1_128 : kSweep2_128; n = 7; }
     else if (D == 256) { cs = kCombos256; n = 5; }
     else return false;
-    for (int i = 0; i < n; ++i) {                     // sorted by padded rows: the first that fits pads least
+    for (int i = 0; i < n; ++i) {
         const int pad = cs[i].NB * 32 * cs[i].WR;
         if (pad >= rows) {
             *out = Plan{cs[i].NB, cs[i].WR, pad, (D == 256) ? 32 : 32 * AUDIOKV_SCORE_KB};
@@ -28,22 +32,14 @@ bool make_plan(int rows, int D, Plan* out) {
     return false;
 }
 
-}  // namespace
-
-int score_padded_rows(int rows, int D) {
-    Plan p;
-    return make_plan(rows, D, &p) ? p.rows_pad : 0;
-}
-
-int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
-    Plan p;
-    if (!make_plan(rows, D, &p) || n_heads_total <= 0) return 1;
+int num_splits(const Plan& p, int n_heads_total, int max_L, int D) {
     // A head is cut into key ranges so that the grid fills the 256 CUs in whole rounds: pick the split
     // count that minimises rounds x (tiles per workgroup + fixed prologue cost, in tiles).
     const int tiles = (max_L + p.tile_keys - 1) / p.tile_keys;
-    // resident workgroups: two per CU when a wave holds one row tile (128 registers, 59 KB of LDS) or the
-    // workgroup is small, one when the eight waves take all the registers
-    const int slots = 256 * ((p.NB == 1 && D <= 128) || p.WR < 7 ? 2 : 1);
+    // resident workgroups per CU: two when the waves are few or hold one row tile each (128 registers), or when
+    // the workgroup is four waves of three row tiles; one when eight waves take all the registers
+    const bool two = (p.NB == 1 && D <= 128) || p.WR < 4 || (p.NB == 3 && p.WR == 3);
+    const int slots = 256 * (two ? 2 : 1);
     const int overhead = 3;
     int best = 1;
     long long best_cost = -1;
@@ -57,20 +53,47 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
     return best;
 }
 
+}  // namespace
+
+int score_padded_rows(int rows, int D) {
+    Plan p1, p2;
+    if (!make_plan(rows, D, 1, &p1) || !make_plan(rows, D, 2, &p2)) return 0;
+    return p1.rows_pad > p2.rows_pad ? p1.rows_pad : p2.rows_pad;
+}
+
+// key ranges per head of sweep 1: what sizes the statistics in the workspace
+int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
+    Plan p;
+    if (!make_plan(rows, D, 1, &p) || n_heads_total <= 0) return 1;
+    return num_splits(p, n_heads_total, max_L, D);
+}
+
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         int max_L, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
                         const float* lse)
 {
-    Plan p;
+    Plan p1, p2;
     const int rows = g.G * g.W;
-    if (!make_plan(rows, g.D, &p)) return hipErrorInvalidValue;
-    const int nsplit = score_num_splits(g.n_items * g.H_kv, max_L, rows, g.D);
-    switch (g.D) {
-        case 64:  return launch_score_d64(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
-        case 128: return launch_score_d128(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
-        case 256: return launch_score_d256(g, p.NB, p.WR, q_win, k, cu_seqlens, nsplit, stats_ws, raw_out, s, between_sweeps, lse);
+    if (!make_plan(rows, g.D, 1, &p1) || !make_plan(rows, g.D, 2, &p2)) return hipErrorInvalidValue;
+    const int n_heads = g.n_items * g.H_kv;
+    const int rows_pad = score_padded_rows(rows, g.D);
+    const int ns1 = num_splits(p1, n_heads, max_L, g.D), ns2 = num_splits(p2, n_heads, max_L, g.D);
+    float* cst = stats_ws + (size_t)n_heads * ns1 * rows_pad * 2;
+    auto sweep = [&](int which, const Plan& p, int ns) -> hipError_t {
+        switch (g.D) {
+            case 64:  return launch_score_d64(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
+            case 128: return launch_score_d128(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
+            case 256: return launch_score_d256(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
+        }
+        return hipErrorInvalidValue;
+    };
+    hipError_t e = sweep(1, p1, ns1);
+    if (e != hipSuccess) return e;
+    if (between_sweeps) {
+        e = hipEventRecord(between_sweeps, s);
+        if (e != hipSuccess) return e;
     }
-    return hipErrorInvalidValue;
+    return sweep(2, p2, ns2);
 }
 
 }  // namespace audiokv

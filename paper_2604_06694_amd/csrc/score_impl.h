@@ -91,11 +91,12 @@ __device__ __forceinline__ int last_visible(const Geom& g, int L, int R, int r) 
 __device__ __forceinline__ constexpr int c_row(int i, int g2) { return (i >> 2) * 8 + g2 * 4 + (i & 3); }
 
 template <int D, int NB, int WR, bool SWEEP2>
-__global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 1) void score_kernel(
+__global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void score_kernel(
     Geom g, const __bf16* __restrict__ q_win, const __bf16* __restrict__ k,
     const int32_t* __restrict__ cu_seq, int nsplit,
-    float* __restrict__ stats,        // sweep 1 out: [head][split][ROWS][2] = (max in base-2 units, sum of exp2)
-    const float* __restrict__ cst,    // sweep 2 in : [head][ROWS] = max + log2(sum), +inf for padded rows
+    int rows_pad,                     // row pitch of stats / cst (>= ROWS: the two sweeps may tile the rows differently)
+    float* __restrict__ stats,        // sweep 1 out: [head][split][rows_pad][2] = (max in base-2 units, sum of exp2)
+    const float* __restrict__ cst,    // sweep 2 in : [head][rows_pad] = max + log2(sum), +inf for padded rows
     float* __restrict__ raw)          // sweep 2 out, packed like scores
 {
     using T = Tile<D, NB, WR>;
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 1) void 
 
     if (t_begin >= t_end) {                           // uniform over the workgroup
         if (!SWEEP2) {
-            float* my_stats = stats + ((size_t)head * nsplit + split) * T::ROWS * 2;
+            float* my_stats = stats + ((size_t)head * nsplit + split) * rows_pad * 2;
             for (int r = tid; r < T::ROWS; r += T::THREADS) { my_stats[2 * r] = -INFINITY; my_stats[2 * r + 1] = 0.f; }
         }
         return;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 1) void 
         }
     }
     if (SWEEP2)
-        for (int r = tid; r < T::ROWS; r += 64 * WR) lds_rc[r] = cst[(size_t)head * T::ROWS + r];
+        for (int r = tid; r < T::ROWS; r += 64 * WR) lds_rc[r] = cst[(size_t)head * rows_pad + r];
 
     // sweep 1: running max (raw logit units) and sum for row row0 + rb*32 + l32 over this lane's keys
     float run_m[NB], run_l[NB];
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 1) void 
 
     if (!SWEEP2) {
         // a row's keys are spread over the two halves of the wave
-        float* my_stats = stats + ((size_t)head * nsplit + split) * T::ROWS * 2;
+        float* my_stats = stats + ((size_t)head * nsplit + split) * rows_pad * 2;
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) {
             const float m2 = __shfl_xor(run_m[rb], 32, 64), l2 = __shfl_xor(run_l[rb], 32, 64);
@@ -494,15 +495,18 @@ static __global__ __launch_bounds__(64) void score_cst_from_lse_kernel(Geom g, c
     cst[(size_t)head * rows_pad + r] = out;
 }
 
+// which = 1: row statistics (sweep 1 and the merge, or the conversion of supplied log-sum-exp values) into
+//            cst = stats + n_heads * nsplit * rows_pad * 2;
+// which = 2: column sums (sweep 2) from the cst at cst_in. The two may use different (NB, WR) tilings and key-range
+// counts: they only share the row pitch rows_pad of the statistics.
 template <int D, int NB, int WR>
-hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seq,
-                              int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
-                              const float* lse)
+hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void* k, const int32_t* cu_seq,
+                        int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
+                        const float* lse)
 {
     using T = Tile<D, NB, WR>;
     const int n_heads = g.n_items * g.H_kv;
     const dim3 grid((unsigned)(n_heads * nsplit));
-    float* cst = stats + (size_t)n_heads * nsplit * T::ROWS * 2;
     static bool attr_set = false;
     if (!attr_set && T::LDS_BYTES > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<D, NB, WR, false>),
@@ -513,35 +517,36 @@ hipError_t launch_both_sweeps(const Geom& g, const void* q_win, const void* k, c
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const unsigned merge_blocks = (unsigned)(n_heads * ((T::ROWS + 63) / 64));
-    if (lse) {
-        hipLaunchKernelGGL(score_cst_from_lse_kernel, dim3(merge_blocks), dim3(64), 0, s, g, lse, T::ROWS, cst);
+    if (which == 1) {
+        const unsigned merge_blocks = (unsigned)(n_heads * ((rows_pad + 63) / 64));
+        if (lse) {
+            hipLaunchKernelGGL(score_cst_from_lse_kernel, dim3(merge_blocks), dim3(64), 0, s, g, lse, rows_pad, cst);
+        } else {
+            hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
+                               (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, stats,
+                               (const float*)nullptr, raw);
+            hipLaunchKernelGGL(score_merge_kernel, dim3(merge_blocks), dim3(64), 0, s, (const float*)stats, nsplit,
+                               rows_pad, g.G * g.W, cst);
+        }
     } else {
-        hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
-                           (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, stats, (const float*)nullptr, raw);
-        hipLaunchKernelGGL(score_merge_kernel, dim3(merge_blocks), dim3(64), 0, s, (const float*)stats, nsplit,
-                           T::ROWS, g.G * g.W, cst);
+        hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
+                           (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, (float*)nullptr,
+                           (const float*)cst, raw);
     }
-    if (between) {
-        const hipError_t e = hipEventRecord(between, s);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
-                       (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, (float*)nullptr, (const float*)cst, raw);
     return hipGetLastError();
 }
 
 }  // namespace score_detail
 
 // one translation unit per head_dim keeps the build parallel
-hipError_t launch_score_d64(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+hipError_t launch_score_d64(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
+        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
         const float* lse);
-hipError_t launch_score_d128(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+hipError_t launch_score_d128(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
+        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
         const float* lse);
-hipError_t launch_score_d256(const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, float* stats, float* raw, hipStream_t s, hipEvent_t between,
+hipError_t launch_score_d256(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
+        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
         const float* lse);
 
 }  // namespace audiokv
