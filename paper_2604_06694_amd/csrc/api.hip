@@ -446,9 +446,8 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     const int n_seg = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? 1 : n_items;
     const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
     const bool prof = g_prof.enabled && g_prof.created;
-    const bool side_filters = !prof && smooth_needs_filters(g, seqlens_host, n_items, cutoff_frac, alpha);
-    // a small pool is allocated faster than a fork and a join are issued: keep it in line then
-    const bool side = !prof && (side_filters || hps >= 32);
+    // a small pool is allocated faster than a fork and a join are issued (55 us of host time): keep it in line then
+    const bool side = !prof && hps >= 32;
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
     AUDIOKV_MARK(0);
     if (!side) {
@@ -461,21 +460,16 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
         AUDIOKV_HIP(hipStreamWaitEvent(g_helper.stream, g_helper.fork, 0), "hipStreamWaitEvent");
         AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
                                     budgets_dev, cu_budgets_dev, g_helper.stream), "allocate kernel");
-        // the smoothing filters of lengths that are not powers of two depend on the lengths only: same side stream
-        if (side_filters)
-            AUDIOKV_HIP(launch_smooth_filters(g, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, ws + w.fft_off,
-                                              g_helper.stream), "smoothing filters");
         AUDIOKV_HIP(hipEventRecord(g_helper.join, g_helper.stream), "hipEventRecord");
     }
     AUDIOKV_MARK(1);
     AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev), "score kernels");
     AUDIOKV_MARK(2);
-    if (side_filters) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // filters (and budgets)
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
-                              alpha, smoothed, ws + w.fft_off, nullptr, false, s, side_filters), "smooth kernel");
+                              alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");
     AUDIOKV_MARK(3);
-    if (side && !side_filters) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
+    if (side) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
     AUDIOKV_MARK(4);

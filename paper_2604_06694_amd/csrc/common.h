@@ -65,7 +65,6 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
                          bool filters_ready = false);
 // Lengths that are not powers of two convolve with filters that depend on the lengths and the cutoff only:
 // launch_smooth_filters prepares them in the workspace (launch_smooth does it itself unless told they are ready).
-bool smooth_needs_filters(const Geom& g, const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha);
 hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const int32_t* seqlens_host, int n_items,
                                  double cutoff_frac, void* workspace, hipStream_t s);
 

@@ -439,6 +439,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
 // ------------------------ arbitrary length: Bluestein over global memory -----------------------
 
 constexpr int kChunkLog = 14;                     // 16384 complex = 128 KiB: the part of an FFT that fits in LDS
+constexpr int kWideMinLog = 12;                   // transforms of 4096 points and more are spread over four workgroups
 constexpr int kMaxBluesteinLog = 16;              // M <= 65536, i.e. L <= 32768
 
 // log2 of the transform size for L samples and K wanted bins: the smallest power of two >= L + K - 1
@@ -631,7 +632,8 @@ __device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
 //   inverse transform (K bins in, L samples out): conj(chirp(m)) for m in (-K, L), which is the first one read
 //   backwards, so its spectrum is the first spectrum at the negated frequency.
 __global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const int32_t* __restrict__ cu_seq, BluesteinWs ws,
-                                                                         double cutoff_frac, int cutoff_mode, int taper_bins)
+                                                                         double cutoff_frac, int cutoff_mode, int taper_bins,
+                                                                         int skip_wide)
 {
     extern __shared__ float smem[];
     const int item = blockIdx.x;
@@ -640,6 +642,7 @@ __global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const in
     const int tid = threadIdx.x;
     const int K = wanted_bins(L, cutoff_frac, cutoff_mode, taper_bins);
     const int logM = bluestein_log(L, K);
+    if (skip_wide && logM >= kWideMinLog) return;     // prepared by the multi-workgroup kernels
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
     cf* z = reinterpret_cast<cf*>(smem);
@@ -671,7 +674,7 @@ __global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const in
 __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
     double cutoff_frac, float alpha, float* __restrict__ out, BluesteinWs ws,
-    int32_t* __restrict__ kstar_out, int cutoffs_only)
+    int32_t* __restrict__ kstar_out, int cutoffs_only, int skip_wide)
 {
     extern __shared__ float smem[];
     const int head = blockIdx.x;
@@ -679,6 +682,8 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const int tok0 = cu_seq[item];
     const int L = cu_seq[item + 1] - tok0;
     if (alpha == 0.f || pow2_length(L)) return;       // the LDS kernel owns this head
+    // all but the small transforms are spread over several workgroups by the kernels below
+    if (skip_wide && bluestein_log(L, wanted_bins(L, cutoff_frac, g.cutoff_mode, g.taper_bins)) >= kWideMinLog) return;
     const size_t off = (size_t)tok0 * g.H_kv + (size_t)h * L;
     const float* src = in + off;
     float* dst = out + off;
@@ -761,6 +766,278 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     }
 }
 
+// ---- transforms of 4096 points and more, spread over several workgroups (fixed-fraction cutoff) -------------------
+// The same convolutions as above, cut at the points where every element of the array has to be complete:
+//   wide_first   chirped input formed on the fly, forward top stage(s)            (one thread per butterfly)
+//   wide_chunk   per chunk of M / 4 points: forward LDS stages, x filter, inverse LDS stages
+//   wide_middle  inverse top stage(s) -> bins; mask; input of the inverse transform; forward top stage(s)
+//   wide_chunk   again, with the second filter
+//   wide_last    inverse top stage(s) -> samples; residual mix; store
+// Few heads (one layer of a prefill) then use 8-64 workgroups per head instead of one.
+
+constexpr int kWideThreads = 256;
+
+struct WideHead {                      // what every kernel of the sequence derives for its head
+    int L, K, logM, M, extra, R, q, owner;
+    size_t off;
+};
+
+__device__ __forceinline__ bool wide_head(const Geom& g, const int32_t* __restrict__ cu_seq, int head, double cutoff_frac,
+                                          WideHead& w) {
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    const int tok0 = cu_seq[item];
+    w.L = cu_seq[item + 1] - tok0;
+    if (pow2_length(w.L)) return false;
+    w.K = wanted_bins(w.L, cutoff_frac, g.cutoff_mode, g.taper_bins);
+    w.logM = bluestein_log(w.L, w.K);
+    if (w.logM < kWideMinLog) return false;            // small: the single-workgroup kernel owns it
+    w.M = 1 << w.logM;
+    w.extra = 2;                                       // two top stages, four chunks of M / 4 <= 16384 points
+    w.R = 1 << w.extra;
+    w.q = w.M >> w.extra;
+    w.owner = owner_item(cu_seq, item, w.L);
+    w.off = (size_t)tok0 * g.H_kv + (size_t)h * w.L;
+    return true;
+}
+
+// exp(-2*pi*i*e/M), e < M/2, straight from the fp32 library (e/M is exact)
+__device__ __forceinline__ cf root_m(int e, int M) {
+    float sn, cs;
+    sincospif(2.0f * (float)e / (float)M, &sn, &cs);
+    return {cs, -sn};
+}
+
+// the top stage(s) on the R values v[r] = x[i + r*q] held in registers (see top_stages for the index algebra)
+__device__ __forceinline__ void top_butterfly(cf* v, int i, int M, int extra, bool inverse) {
+    if (extra == 1) {
+        const cf w = root_m(i, M);
+        if (!inverse) { const cf d = csub(v[0], v[1]); v[0] = cadd(v[0], v[1]); v[1] = cmul(d, w); }
+        else { const cf cw = cmul(v[1], cconj(w)); v[1] = csub(v[0], cw); v[0] = cadd(v[0], cw); }
+        return;
+    }
+    const cf w1 = root_m(i, M), w2 = root_m(2 * i, M);
+    cf a0 = v[0], a1 = v[1], a2 = v[2], a3 = v[3];
+    if (!inverse) {
+        const cf b0 = cadd(a0, a2), b2 = cmul(csub(a0, a2), w1);
+        const cf b1 = cadd(a1, a3), b3 = mul_neg_i(cmul(csub(a1, a3), w1));
+        a0 = cadd(b0, b1); a1 = cmul(csub(b0, b1), w2);
+        a2 = cadd(b2, b3); a3 = cmul(csub(b2, b3), w2);
+    } else {
+        const cf w1c = cconj(w1), w2c = cconj(w2);
+        const cf t1 = cmul(a1, w2c), t3 = cmul(a3, w2c);
+        const cf b0 = cadd(a0, t1), b1 = csub(a0, t1), b2 = cadd(a2, t3), b3 = csub(a2, t3);
+        const cf u2 = cmul(b2, w1c), u3 = mul_pos_i(cmul(b3, w1c));
+        a0 = cadd(b0, u2); a2 = csub(b0, u2);
+        a1 = cadd(b1, u3); a3 = csub(b1, u3);
+    }
+    v[0] = a0; v[1] = a1; v[2] = a2; v[3] = a3;
+}
+
+// preparation of the filters of a wide transform, spread the same way: chirp table; wrapped filter + forward top
+// stage(s); chunk-local stages (wide_chunk_kernel, which_filter = -1); second filter by the frequency-negating gather.
+// Grids run over the first head of every item; only items that own their length work.
+__device__ __forceinline__ bool wide_owner(const Geom& g, const int32_t* __restrict__ cu_seq, int item, double cutoff_frac,
+                                           WideHead& w) {
+    return wide_head(g, cu_seq, item * g.H_kv, cutoff_frac, w) && w.owner == item;
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_prep_chirp_kernel(Geom g, const int32_t* __restrict__ cu_seq,
+                                                                       double cutoff_frac, BluesteinWs ws)
+{
+    WideHead w;
+    const int item = blockIdx.y;
+    if (!wide_owner(g, cu_seq, item, cutoff_frac, w)) return;
+    cf* ch = ws.chirp_of(item);
+    for (int n = blockIdx.x * kWideThreads + threadIdx.x; n < w.L; n += gridDim.x * kWideThreads) ch[n] = chirp(n, w.L);
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_prep_first_kernel(Geom g, const int32_t* __restrict__ cu_seq,
+                                                                       double cutoff_frac, BluesteinWs ws)
+{
+    WideHead w;
+    const int item = blockIdx.y;
+    if (!wide_owner(g, cu_seq, item, cutoff_frac, w)) return;
+    const int i = blockIdx.x * kWideThreads + threadIdx.x;
+    if (i >= w.q) return;
+    const cf* ch = ws.chirp_of(item);
+    cf* B1 = ws.bhat_of(item, 0);
+    cf v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int n = i + r * w.q;
+        cf b = {0.f, 0.f};
+        if (r < w.R) {
+            if (n < w.K) b = cconj(ch[n]);
+            else if (n > w.M - w.L) b = cconj(ch[w.M - n]);
+        }
+        v[r] = b;
+    }
+    top_butterfly(v, i, w.M, w.extra, false);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (r < w.R) B1[i + r * w.q] = v[r];
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_prep_second_kernel(Geom g, const int32_t* __restrict__ cu_seq,
+                                                                        double cutoff_frac, BluesteinWs ws)
+{
+    WideHead w;
+    const int item = blockIdx.y;
+    if (!wide_owner(g, cu_seq, item, cutoff_frac, w)) return;
+    const cf* B1 = ws.bhat_of(item, 0);
+    cf* B2 = ws.bhat_of(item, 1);
+    const int shift = 32 - w.logM;
+    for (int p = blockIdx.x * kWideThreads + threadIdx.x; p < w.M; p += gridDim.x * kWideThreads) {
+        const unsigned f = __brev((unsigned)p) >> shift;
+        const unsigned nf = (w.M - f) & (w.M - 1);
+        B2[p] = B1[__brev(nf) >> shift];
+    }
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_first_kernel(
+    Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac,
+    BluesteinWs ws)
+{
+    WideHead w;
+    const int head = blockIdx.y;
+    if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    const int i = blockIdx.x * kWideThreads + threadIdx.x;
+    if (i >= w.q) return;
+    const float* src = in + w.off;
+    const cf* ch = ws.chirp_of(w.owner);
+    cf* A = ws.a_of(head);
+    cf v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (r >= w.R) break;
+        const int n = i + r * w.q;
+        cf a = {0.f, 0.f};
+        if (n < w.L) {
+            const cf c = ch[n];
+            const float sv = pool_on_load ? pooled_at(src, w.L, n, g.pool_kernel, g.pool_mode) : src[n];
+            a = {sv * c.re, sv * c.im};
+        }
+        v[r] = a;
+    }
+    top_butterfly(v, i, w.M, w.extra, false);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (r < w.R) A[i + r * w.q] = v[r];
+}
+
+__global__ __launch_bounds__(kFftThreads) void wide_chunk_kernel(
+    Geom g, const int32_t* __restrict__ cu_seq, double cutoff_frac, BluesteinWs ws, int which_filter)
+{
+    extern __shared__ float smem[];
+    WideHead w;
+    const int head = blockIdx.y;
+    if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    const int chunk = blockIdx.x;
+    if (chunk >= w.R) return;
+    const int logC = w.logM - w.extra;
+    const int C = 1 << logC;
+    cf* z = reinterpret_cast<cf*>(smem);
+    cf* lo = z + padded_len(C);
+    cf* hi = lo + kTwLo;
+    fill_tables(lo, hi, (w.M >> 8) + 1, w.M);
+    if (which_filter < 0) {
+        // preparation: chunk-local forward stages of the first filter itself (one head per item does it)
+        const int item = head / g.H_kv;
+        if (head != item * g.H_kv || w.owner != item) return;
+        cf* b = ws.bhat_of(item, 0) + (size_t)chunk * C;
+        chunk_load(z, b, C);
+        fft_lds(z, logC, w.logM - 1, false, lo, hi);
+        chunk_store(b, z, C);
+        return;
+    }
+    cf* x = ws.a_of(head) + (size_t)chunk * C;
+    const cf* bhat = ws.bhat_of(w.owner, which_filter) + (size_t)chunk * C;
+    chunk_load(z, x, C);                                // ends with a barrier: the tables are complete too
+    fft_lds(z, logC, w.logM - 1, false, lo, hi);
+    for (int i = 2 * threadIdx.x; i < C; i += 2 * kFftThreads) {
+        cf b0, b1;
+        ld2(bhat, i, b0, b1);
+        z[pad(i)] = cmul(z[pad(i)], b0);
+        z[pad(i + 1)] = cmul(z[pad(i + 1)], b1);
+    }
+    __syncthreads();
+    fft_lds(z, logC, w.logM - 1, true, lo, hi);
+    chunk_store(x, z, C);
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_middle_kernel(
+    Geom g, const int32_t* __restrict__ cu_seq, double cutoff_frac, BluesteinWs ws, int32_t* __restrict__ kstar_out)
+{
+    WideHead w;
+    const int head = blockIdx.y;
+    if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    const int i = blockIdx.x * kWideThreads + threadIdx.x;
+    const int kstar = (int)floor(cutoff_frac * (double)(w.L >> 1));
+    if (kstar_out && i == 0) kstar_out[head] = kstar;
+    if (i >= w.q) return;
+    const cf* ch = ws.chirp_of(w.owner);
+    cf* A = ws.a_of(head);
+    const float inv_m = 1.0f / (float)w.M;
+    const int T = g.taper_bins;
+    cf v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
+    top_butterfly(v, i, w.M, w.extra, true);            // v[r] is now the convolution at position k = i + r*q
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (r >= w.R) break;
+        const int k = i + r * w.q;
+        cf o = {0.f, 0.f};
+        if (k < w.K) {
+            const float wgt = mask_weight(k, kstar, T) * ((k == 0 || 2 * k == w.L) ? 1.f : 2.f);
+            if (wgt > 0.f) {
+                const cf c = ch[k];
+                cf F = cmul(c, v[r]);
+                F = {F.re * inv_m * wgt, F.im * inv_m * wgt};
+                o = cmul(cconj(F), c);
+            }
+        }
+        v[r] = o;
+    }
+    top_butterfly(v, i, w.M, w.extra, false);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (r < w.R) A[i + r * w.q] = v[r];
+}
+
+__global__ __launch_bounds__(kWideThreads) void wide_last_kernel(
+    Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac,
+    float alpha, float* __restrict__ out, BluesteinWs ws)
+{
+    WideHead w;
+    const int head = blockIdx.y;
+    if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    const int i = blockIdx.x * kWideThreads + threadIdx.x;
+    if (i >= w.q) return;
+    const float* src = in + w.off;
+    float* dst = out + w.off;
+    const cf* ch = ws.chirp_of(w.owner);
+    const cf* A = ws.a_of(head);
+    const float scale = 1.0f / (float)w.M / (float)w.L;
+    cf v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
+    top_butterfly(v, i, w.M, w.extra, true);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        if (r >= w.R) break;
+        const int n = i + r * w.q;
+        if (n >= w.L) continue;
+        const cf y = cmul(ch[n], v[r]);
+        const float st = y.re * scale;
+        if (alpha == 1.f) dst[n] = st;
+        else {
+            const float s0 = pool_on_load ? pooled_at(src, w.L, n, g.pool_kernel, g.pool_mode) : src[n];
+            dst[n] = (1.f - alpha) * s0 + alpha * st;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
@@ -809,6 +1086,9 @@ hipError_t smooth_kernel_attributes() {
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(bluestein_prepare_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(wide_chunk_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess) attr_set = true;
     return e;
 }
@@ -820,10 +1100,6 @@ size_t bluestein_smem(const Geom& g, size_t M) {
 }
 }  // namespace
 
-bool smooth_needs_filters(const Geom& g, const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha) {
-    return alpha != 0.0 && plan_smooth(g, seqlens_host, n_items, cutoff_frac).max_log > 0;
-}
-
 hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const int32_t* seqlens_host, int n_items,
                                  double cutoff_frac, void* workspace, hipStream_t s)
 {
@@ -834,8 +1110,19 @@ hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const
     if (e != hipSuccess) return e;
     const size_t M = (size_t)1 << pl.max_log;
     const BluesteinWs bw{static_cast<cf*>(workspace), M, g.n_items * g.H_kv};
+    const bool wide = pl.max_log >= kWideMinLog;
     hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), bluestein_smem(g, M), s, cu_seqlens,
-                       bw, cutoff_frac, g.cutoff_mode, g.taper_bins);
+                       bw, cutoff_frac, g.cutoff_mode, g.taper_bins, wide ? 1 : 0);
+    if (wide) {
+        const int extra_stages = 2;
+        const unsigned q = (unsigned)(M >> extra_stages);
+        const dim3 ew((q + kWideThreads - 1) / kWideThreads, (unsigned)g.n_items);
+        hipLaunchKernelGGL(wide_prep_chirp_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
+        hipLaunchKernelGGL(wide_prep_first_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
+        hipLaunchKernelGGL(wide_chunk_kernel, dim3((unsigned)1 << extra_stages, (unsigned)(g.n_items * g.H_kv)),
+                           dim3(kFftThreads), bluestein_smem(g, M), s, g, cu_seqlens, cutoff_frac, bw, -1);
+        hipLaunchKernelGGL(wide_prep_second_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
+    }
     return hipGetLastError();
 }
 
@@ -868,9 +1155,26 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         }
         const size_t M = (size_t)1 << max_log;
         const BluesteinWs bw{static_cast<cf*>(workspace), M, n_heads};
+        // transforms wider than one LDS chunk go to the multi-workgroup sequence, unless the cutoff has to be found
+        // from the whole spectrum first
+        const bool wide = max_log >= kWideMinLog && g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && !cutoffs_only;
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), bluestein_smem(g, M), s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
-                           cutoffs_only ? 1 : 0);
+                           cutoffs_only ? 1 : 0, wide ? 1 : 0);
+        if (wide) {
+            const int extra_stages = 2;
+            const unsigned q = (unsigned)(M >> extra_stages);
+            const dim3 ew((q + kWideThreads - 1) / kWideThreads, (unsigned)n_heads);
+            const dim3 cw((unsigned)1 << extra_stages, (unsigned)n_heads);
+            const size_t csm = bluestein_smem(g, M);
+            hipLaunchKernelGGL(wide_first_kernel, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
+                               cutoff_frac, bw);
+            hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 0);
+            hipLaunchKernelGGL(wide_middle_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw, kstar_out);
+            hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 1);
+            hipLaunchKernelGGL(wide_last_kernel, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
+                               cutoff_frac, (float)alpha, out, bw);
+        }
     }
     return hipGetLastError();
 }
