@@ -107,7 +107,8 @@ Geom make_geom(const audiokv_params* p, int n_items) {
 }
 
 struct Workspace {
-    size_t stats_off = 0, raw_off = 0, smooth_off = 0, fft_off = 0, total = 0;
+    size_t stats_off = 0, raw_off = 0, raw2_off = 0, smooth_off = 0, fft_off = 0, total = 0;
+    bool raw2 = false;
 };
 
 Workspace plan_workspace(const audiokv_params* p, const Batch& b, const int32_t* seqlens_host) {
@@ -122,6 +123,9 @@ Workspace plan_workspace(const audiokv_params* p, const Batch& b, const int32_t*
     off += align_up((size_t)n_heads * (rows_pad > 0 ? rows_pad : 1) * (2 * (size_t)nsplit + 1) * sizeof(float), 256);
     w.raw_off = off;
     off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
+    w.raw2 = score_needs_second_raw(rows, p->head_dim);     // second row range of a split sweep 2
+    w.raw2_off = off;
+    if (w.raw2) off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
     w.smooth_off = off;
     off += align_up((size_t)b.total_tokens * p->n_kv_heads * sizeof(float), 256);
     w.fft_off = off;          // arbitrary-length spectral smoothing (empty when every length is a power of two)
@@ -163,7 +167,7 @@ int32_t check_score_shape(const audiokv_params* p) {
     const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
     if (score_padded_rows(rows, p->head_dim) == 0)
         return fail(AUDIOKV_E_UNSUPPORTED, "group * window = %d rows at head_dim %d exceeds what the score kernels hold "
-                    "in registers (512 rows at d <= 128, 256 rows at d = 256)", rows, p->head_dim);
+                    "in registers (576 rows at d <= 128, 256 rows at d = 256)", rows, p->head_dim);
     return AUDIOKV_OK;
 }
 
@@ -259,7 +263,9 @@ int32_t score_entry(const audiokv_params* params, const void* q_win, const void*
     char* ws = static_cast<char*>(workspace);
     float* stats = reinterpret_cast<float*>(ws + w.stats_off);
     float* raw = params->pool_kernel == 1 ? scores : reinterpret_cast<float*>(ws + w.raw_off);
-    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s, nullptr, lse_dev), "score kernels");
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s, nullptr, lse_dev,
+                             w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
+                             (size_t)b.total_tokens * params->n_kv_heads), "score kernels");
     if (params->pool_kernel != 1)
         AUDIOKV_HIP(launch_pool(g, raw, cu_seqlens_dev, b.max_L, scores, s), "pool kernel");
     return AUDIOKV_OK;
@@ -464,7 +470,9 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     }
     AUDIOKV_MARK(1);
     AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
-                             prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev), "score kernels");
+                             prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev,
+                             w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
+                             (size_t)b.total_tokens * params->n_kv_heads), "score kernels");
     AUDIOKV_MARK(2);
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");

@@ -46,7 +46,11 @@ int score_padded_rows(int rows, int D);
 // lse: optional fp32 [items][H_q][W] natural-log softmax denominators of the window rows; given, sweep 1 is skipped.
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         int max_L, float* stats_ws, float* raw_out, hipStream_t s,
-                        hipEvent_t between_sweeps = nullptr, const float* lse = nullptr);
+                        hipEvent_t between_sweeps = nullptr, const float* lse = nullptr,
+                        float* raw_second = nullptr, size_t raw_elems = 0);
+// More than 448 window rows (d <= 128): sweep 2 runs as two launches and needs a second buffer of the size of the
+// scores (raw_second, raw_elems floats).
+bool score_needs_second_raw(int rows, int D);
 hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlens, int max_L,
                        float* pooled, hipStream_t s);
 

@@ -55,11 +55,26 @@ int num_splits(const Plan& p, int n_heads_total, int max_L, int D) {
 
 }  // namespace
 
+// Sweep 2 cannot hold more than 448 rows without spilling (its row constants come on top of the accumulators), so
+// more rows are covered by two launches: the first 448 with the widest tiling, the rest with the smallest that fits;
+// the second writes its column sums to a buffer of its own, added to the first afterwards.
+constexpr int kSweep2MaxRows = 448;
+
+bool sweep2_is_split(int rows, int D) { return D <= 128 && rows > kSweep2MaxRows; }
+
 int score_padded_rows(int rows, int D) {
     Plan p1, p2;
-    if (!make_plan(rows, D, 1, &p1) || !make_plan(rows, D, 2, &p2)) return 0;
+    if (!make_plan(rows, D, 1, &p1)) return 0;
+    if (sweep2_is_split(rows, D)) {
+        if (!make_plan(rows - kSweep2MaxRows, D, 2, &p2)) return 0;
+        const int pad2 = kSweep2MaxRows + p2.rows_pad;
+        return p1.rows_pad > pad2 ? p1.rows_pad : pad2;
+    }
+    if (!make_plan(rows, D, 2, &p2)) return 0;
     return p1.rows_pad > p2.rows_pad ? p1.rows_pad : p2.rows_pad;
 }
+
+bool score_needs_second_raw(int rows, int D) { return sweep2_is_split(rows, D); }
 
 // key ranges per head of sweep 1: what sizes the statistics in the workspace
 int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
@@ -70,30 +85,46 @@ int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
 
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         int max_L, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
-                        const float* lse)
+                        const float* lse, float* raw_second, size_t raw_elems)
 {
-    Plan p1, p2;
+    Plan p1;
     const int rows = g.G * g.W;
-    if (!make_plan(rows, g.D, 1, &p1) || !make_plan(rows, g.D, 2, &p2)) return hipErrorInvalidValue;
+    if (!make_plan(rows, g.D, 1, &p1)) return hipErrorInvalidValue;
     const int n_heads = g.n_items * g.H_kv;
     const int rows_pad = score_padded_rows(rows, g.D);
-    const int ns1 = num_splits(p1, n_heads, max_L, g.D), ns2 = num_splits(p2, n_heads, max_L, g.D);
+    if (rows_pad == 0) return hipErrorInvalidValue;
+    const int ns1 = num_splits(p1, n_heads, max_L, g.D);
     float* cst = stats_ws + (size_t)n_heads * ns1 * rows_pad * 2;
-    auto sweep = [&](int which, const Plan& p, int ns) -> hipError_t {
+    auto sweep = [&](int which, const Plan& p, int ns, int row_base, float* raw) -> hipError_t {
         switch (g.D) {
-            case 64:  return launch_score_d64(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
-            case 128: return launch_score_d128(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
-            case 256: return launch_score_d256(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, stats_ws, cst, raw_out, s, lse);
+            case 64:  return launch_score_d64(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, row_base, stats_ws, cst, raw, s, lse);
+            case 128: return launch_score_d128(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, row_base, stats_ws, cst, raw, s, lse);
+            case 256: return launch_score_d256(which, g, p.NB, p.WR, q_win, k, cu_seqlens, ns, rows_pad, row_base, stats_ws, cst, raw, s, lse);
         }
         return hipErrorInvalidValue;
     };
-    hipError_t e = sweep(1, p1, ns1);
+    hipError_t e = sweep(1, p1, ns1, 0, raw_out);
     if (e != hipSuccess) return e;
     if (between_sweeps) {
         e = hipEventRecord(between_sweeps, s);
         if (e != hipSuccess) return e;
     }
-    return sweep(2, p2, ns2);
+    Plan p2;
+    if (!sweep2_is_split(rows, g.D)) {
+        if (!make_plan(rows, g.D, 2, &p2)) return hipErrorInvalidValue;
+        return sweep(2, p2, num_splits(p2, n_heads, max_L, g.D), 0, raw_out);
+    }
+    if (!raw_second) return hipErrorInvalidValue;
+    Plan p2b;
+    if (!make_plan(kSweep2MaxRows, g.D, 2, &p2) || !make_plan(rows - kSweep2MaxRows, g.D, 2, &p2b)) return hipErrorInvalidValue;
+    e = sweep(2, p2, num_splits(p2, n_heads, max_L, g.D), 0, raw_out);
+    if (e != hipSuccess) return e;
+    e = sweep(2, p2b, num_splits(p2b, n_heads, max_L, g.D), kSweep2MaxRows, raw_second);
+    if (e != hipSuccess) return e;
+    const unsigned blocks = (unsigned)((raw_elems + 256 * 8 - 1) / (256 * 8));
+    hipLaunchKernelGGL(score_detail::score_add_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, s, raw_out,
+                       (const float*)raw_second, raw_elems);
+    return hipGetLastError();
 }
 
 }  // namespace audiokv

@@ -95,6 +95,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     Geom g, const __bf16* __restrict__ q_win, const __bf16* __restrict__ k,
     const int32_t* __restrict__ cu_seq, int nsplit,
     int rows_pad,                     // row pitch of stats / cst (>= ROWS: the two sweeps may tile the rows differently)
+    int row_base,                     // first window row of this launch (sweep 2 may cover the rows in two launches)
     float* __restrict__ stats,        // sweep 1 out: [head][split][rows_pad][2] = (max in base-2 units, sum of exp2)
     const float* __restrict__ cst,    // sweep 2 in : [head][rows_pad] = max + log2(sum), +inf for padded rows
     float* __restrict__ raw)          // sweep 2 out, packed like scores
@@ -131,7 +132,8 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, g2 = lane >> 5;
-    const int row0 = wave * NB * 32;
+    const int row0 = wave * NB * 32;                  // first row of this wave inside the launch's row range
+    const int rowg0 = row_base + row0;                // the same as a window row of the head
 
     const int n_tiles = (L + T::TK - 1) / T::TK;
     const int tps = (n_tiles + nsplit - 1) / nsplit;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     bf16x8 qf[NB][T::KK];
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) {
-        const int r = row0 + rb * 32 + l32;
+        const int r = rowg0 + rb * 32 + l32;
         const bool live = r < R;
         const int qh = live ? r / g.W : 0, wrow = live ? r - qh * g.W : 0;
         const __bf16* src = q_win + (((size_t)item * g.H_q + (size_t)h * g.G + qh) * g.W + wrow) * D + g2 * 8;
@@ -224,7 +226,8 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         }
     }
     if (SWEEP2)
-        for (int r = tid; r < T::ROWS; r += 64 * WR) lds_rc[r] = cst[(size_t)head * rows_pad + r];
+        for (int r = tid; r < T::ROWS; r += 64 * WR)
+            lds_rc[r] = row_base + r < rows_pad ? cst[(size_t)head * rows_pad + row_base + r] : INFINITY;
 
     // sweep 1: running max (raw logit units) and sum for row row0 + rb*32 + l32 over this lane's keys
     float run_m[NB], run_l[NB];
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
                 if (MASKED) {
-                    const int lv = last_visible(g, L, R, row0 + rb * 32 + l32);
+                    const int lv = last_visible(g, L, R, rowg0 + rb * 32 + l32);
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         if (j0b + c_row(i, g2) > lv) a[rb][i] = -INFINITY;
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
             for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (j0b + l32 > last_visible(g, L, R, row0 + rb * 32 + c_row(i, g2))) a[rb][i] = -INFINITY;
+                    if (j0b + l32 > last_visible(g, L, R, rowg0 + rb * 32 + c_row(i, g2))) a[rb][i] = -INFINITY;
         }
     };
     auto reduce_slice = [&](f32x16 (&a)[NB], int sl) {  // elements [sl*SLICE, (sl+1)*SLICE) of every row tile
@@ -434,7 +437,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
             const float m2 = __shfl_xor(run_m[rb], 32, 64), l2 = __shfl_xor(run_l[rb], 32, 64);
             merge_stats(run_m[rb], run_l[rb], m2, l2, c);
             if (g2 == 0) {
-                const int r = row0 + rb * 32 + l32;
+                const int r = rowg0 + rb * 32 + l32;
                 my_stats[2 * r] = (run_m[rb] == -INFINITY) ? -INFINITY : run_m[rb] * c;
                 my_stats[2 * r + 1] = run_l[rb];
             }
@@ -495,13 +498,19 @@ static __global__ __launch_bounds__(64) void score_cst_from_lse_kernel(Geom g, c
     cst[(size_t)head * rows_pad + r] = out;
 }
 
+// raw += raw_b: the column sums of the second row range of a split sweep 2 (fixed order: deterministic)
+static __global__ __launch_bounds__(256) void score_add_kernel(float* __restrict__ raw, const float* __restrict__ raw_b, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) raw[i] += raw_b[i];
+}
+
 // which = 1: row statistics (sweep 1 and the merge, or the conversion of supplied log-sum-exp values) into
 //            cst = stats + n_heads * nsplit * rows_pad * 2;
 // which = 2: column sums (sweep 2) from the cst at cst_in. The two may use different (NB, WR) tilings and key-range
 // counts: they only share the row pitch rows_pad of the statistics.
 template <int D, int NB, int WR>
 hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void* k, const int32_t* cu_seq,
-                        int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
+                        int nsplit, int rows_pad, int row_base, float* stats, float* cst, float* raw, hipStream_t s,
                         const float* lse)
 {
     using T = Tile<D, NB, WR>;
@@ -523,14 +532,14 @@ hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void*
             hipLaunchKernelGGL(score_cst_from_lse_kernel, dim3(merge_blocks), dim3(64), 0, s, g, lse, rows_pad, cst);
         } else {
             hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
-                               (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, stats,
+                               (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, 0, stats,
                                (const float*)nullptr, raw);
             hipLaunchKernelGGL(score_merge_kernel, dim3(merge_blocks), dim3(64), 0, s, (const float*)stats, nsplit,
                                rows_pad, g.G * g.W, cst);
         }
     } else {
         hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
-                           (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, (float*)nullptr,
+                           (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, row_base, (float*)nullptr,
                            (const float*)cst, raw);
     }
     return hipGetLastError();
@@ -540,13 +549,13 @@ hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void*
 
 // one translation unit per head_dim keeps the build parallel
 hipError_t launch_score_d64(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
-        const float* lse);
+        const int32_t* cu_seq, int nsplit, int rows_pad, int row_base, float* stats, float* cst, float* raw,
+        hipStream_t s, const float* lse);
 hipError_t launch_score_d128(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
-        const float* lse);
+        const int32_t* cu_seq, int nsplit, int rows_pad, int row_base, float* stats, float* cst, float* raw,
+        hipStream_t s, const float* lse);
 hipError_t launch_score_d256(int which, const Geom& g, int NB, int WR, const void* q_win, const void* k,
-        const int32_t* cu_seq, int nsplit, int rows_pad, float* stats, float* cst, float* raw, hipStream_t s,
-        const float* lse);
+        const int32_t* cu_seq, int nsplit, int rows_pad, int row_base, float* stats, float* cst, float* raw,
+        hipStream_t s, const float* lse);
 
 }  // namespace audiokv

@@ -268,7 +268,7 @@ def _score_case(A, H_q, H_kv, W, d, lens, *, causal=1, layout=0, pool_kernel=7, 
 @pytest.mark.parametrize("H_q,H_kv,W,d", [(28, 4, 32, 128), (32, 4, 32, 128), (8, 2, 32, 256), (4, 2, 8, 64),
                                           (14, 2, 64, 128), (2, 2, 16, 128), (3, 1, 5, 64),
                                           (16, 2, 64, 128), (16, 2, 64, 64), (9, 1, 32, 128), (8, 1, 33, 64),
-                                          (8, 1, 32, 256)])
+                                          (8, 1, 32, 256), (9, 1, 64, 128), (15, 1, 32, 64)])
 def test_score_parity_shapes(A, H_q, H_kv, W, d):
     _score_case(A, H_q, H_kv, W, d, [1000], seed=H_q + W)
 
