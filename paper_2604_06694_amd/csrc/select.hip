@@ -2,12 +2,14 @@
 // Top-K selection on the importance scores; window w of Sec. 3.1 Eq. 1).
 //
 // One workgroup per head. Scores become order-preserving 32-bit keys held in
-// registers (a contiguous run of tokens per thread, staged through padded LDS
-// so that both the global read and the per-thread read are conflict-free).
+// registers (token t + 1024 e in register e of thread t: coalesced loads).
 // The value of the k-th largest key is found bit by bit (32 counting passes,
-// no atomics); tokens above it are kept, tokens equal to it are kept in index
-// order until the budget is full, and kept indices are written in ascending
-// order through a block-wide exclusive scan (gathered in LDS, stored coalesced).
+// no atomics); once the keys that the remaining bits can still separate are
+// few, they are moved to a short list and only they are counted. Tokens above
+// the threshold are kept, tokens equal to it are kept in index order until the
+// budget is full: per-token bitmaps built from lane masks give every thread 32
+// consecutive tokens back, and kept indices are written in ascending order
+// through a block-wide exclusive scan (gathered in LDS, stored coalesced).
 // Integer-only: bit-exact.
 #include "common.h"
 
@@ -59,19 +61,25 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int* slots /* 2*kSel
     eb = pb + ib - b;
 }
 
+constexpr int kCompact = 4;          // undecided keys per thread once the candidates have been narrowed down
+
 template <int EPT>   // tokens per thread; the head must have at most EPT * kSelThreads candidates
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     Geom g, const float* __restrict__ scores, const int32_t* __restrict__ budgets,
     const int32_t* __restrict__ cu_b, const int32_t* __restrict__ cu_seq, int32_t* __restrict__ indices)
 {
-    extern __shared__ float stage[];                 // EPT*kSelThreads floats + 1 pad per 32
+    extern __shared__ int32_t lds_out[];             // kept indices at their output slots (up to EPT*kSelThreads)
     __shared__ int slots[4 * kSelWaves];
+    __shared__ int pass_count[3];
+    __shared__ uint32_t narrowed[kCompact * kSelThreads];               // keys still undecided after narrowing
+    __shared__ uint32_t gt_words[kSelThreads + 2], eq_words[kSelThreads + 2];   // one bit per token, 32 tokens per word
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
     const int L = cu_seq[item + 1] - tok0;
     const float* s = scores + (size_t)tok0 * g.H_kv + (size_t)h * L;
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
 
     const int W = min(g.W, L);
     const int n_cand = L - W;
@@ -87,61 +95,110 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     if (want <= 0) return;
     if (n_cand > EPT * kSelThreads) return;          // launcher never allows this
 
-    // global (coalesced) -> padded LDS -> registers (thread t owns tokens [t*EPT, t*EPT+EPT))
-    for (int j = tid; j < n_cand; j += kSelThreads) stage[j + (j >> 5)] = s[j];
-    __syncthreads();
+    // Thread t holds tokens t, t + 1024, t + 2048, ...: the loads are coalesced straight into registers, a thread's
+    // keys are spread over the whole sequence (so the undecided ones stay evenly spread, see below), and for a fixed
+    // register the lanes of a wave hold 64 consecutive tokens (so one lane mask is 64 bits of a per-token bitmap).
     uint32_t key[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const int j = tid * EPT + e;
-        key[e] = j < n_cand ? order_key(stage[j + (j >> 5)]) : 0u;   // 0 is below every real key
+        const int j = tid + e * kSelThreads;
+        // clamped address and a mask instead of a branch around the load: all loads of a thread are in flight together
+        const float f = s[min(j, n_cand - 1)];
+        key[e] = order_key(f) & (j < n_cand ? 0xffffffffu : 0u);   // 0 is below every real key and every trial
     }
 
-    // k-th largest key: the largest T with #(key >= T) >= want
+    // k-th largest key: the largest T with #(key >= T) >= want, found bit by bit. c_lo = #(key >= T) and
+    // c_up = #(key >= T + 2^bit) bracket the keys whose upper bits equal T's: the only ones later bits can still
+    // tell apart. Once they are few they are moved to a short list, kCompact per thread, and the remaining passes
+    // count only those; the keys above the bracket are a constant.
+    if (tid < 3) pass_count[tid] = 0;
+    __syncthreads();
     uint32_t T = 0;
+    int c_lo = n_cand, c_up = 0;
     int parity = 0;
-    for (int bit = 31; bit >= 0; --bit) {
+    // One counting pass: `c` is this wave's count of keys >= trial (wave-uniform). The block-wide sum goes through
+    // one LDS counter per pass (three in rotation: the counter of the next pass was last read two passes ago,
+    // before the previous barrier, so it is cleared while this one is in use). Integer adds: order-free.
+    auto decide = [&](uint32_t trial, int c, int c_above) {
+        if (lane == 0) atomicAdd(&pass_count[parity], c);
+        if (tid == 0) pass_count[parity == 2 ? 0 : parity + 1] = 0;
+        __syncthreads();
+        const int t = c_above + pass_count[parity];
+        if (t >= want) { T = trial; c_lo = t; } else { c_up = t; }
+        parity = parity == 2 ? 0 : parity + 1;
+    };
+    int bit = 31;
+    bool narrow = false;
+    for (; bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
         // wave-wide count on the scalar unit: one compare per key, its lane mask counted with a population count
         int c = 0;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= trial));
-        int* sl = slots + parity * kSelWaves;
-        if ((tid & 63) == 0) sl[tid >> 6] = c;
-        __syncthreads();
-        int t = 0;
+        decide(trial, c, 0);
+        // Few undecided keys left (uniform decision)? T >> bit != 0 keeps the padding key 0 out of the bracket.
+        if (EPT > kCompact && bit > 0 && (T >> bit) != 0u && c_lo - c_up <= kCompact * kSelThreads) { narrow = true; break; }
+    }
+    if (narrow) {
+        // move the real keys in [T, T + 2^bit) to the short list, kCompact per thread, evenly spread
+        const uint32_t hi_part = T >> bit;
+        int mine = 0;
 #pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) t += sl[w];
-        if (t >= want) T = trial;
-        parity ^= 1;
+        for (int e = 0; e < EPT; ++e) mine += (key[e] >> bit) == hi_part ? 1 : 0;
+        int before, unused;
+        block_exscan2(mine, 0, slots + 2 * kSelWaves, before, unused);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            if ((key[e] >> bit) == hi_part) narrowed[before++] = key[e];
+        __syncthreads();
+        const int n_und = c_lo - c_up;
+        const int c_above = c_up;                    // keys above the bracket: counted in every later pass
+        uint32_t ckey[kCompact];
+#pragma unroll
+        for (int e = 0; e < kCompact; ++e) {
+            const int i = tid + e * kSelThreads;
+            ckey[e] = i < n_und ? narrowed[i] : 0u;
+        }
+        for (--bit; bit >= 0; --bit) {
+            const uint32_t trial = T | (1u << bit);
+            int c = 0;
+#pragma unroll
+            for (int e = 0; e < kCompact; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ckey[e] >= trial));
+            decide(trial, c, c_above);
+        }
     }
     // tokens strictly above T all stay; tokens equal to T stay in index order while room is left
-    int c_gt = 0, c_eq = 0;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-        const int j = tid * EPT + e;
-        const bool live = j < n_cand;
-        c_gt += (live && key[e] > T) ? 1 : 0;
-        c_eq += (live && key[e] == T) ? 1 : 0;
-    }
-    int gt_before, eq_before;
-    block_exscan2(c_gt, c_eq, slots + 2 * kSelWaves, gt_before, eq_before);
-    const int total_gt = block_count(c_gt, slots, parity);
-    const int need_eq = want - total_gt;             // >= 1 by construction of T
+    const int need_eq = want - c_up;                 // c_up = #(key > T); >= 1 by construction of T
 
-    // Kept indices are gathered in LDS at their output slots (the staging buffer is free: the keys live in
-    // registers) and then written out in one coalesced sweep; written straight from here, every store of a wave
-    // would touch 64 different cache lines.
-    int32_t* lds_out = reinterpret_cast<int32_t*>(stage);
-    __syncthreads();                                 // all reads of the staged scores are long done; be explicit
+    // per-token bitmaps of (key > T) and (key == T) from lane masks: wave w, register e covers tokens
+    // [e*1024 + w*64, +64)
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const int j = tid * EPT + e;
-        if (j >= n_cand) break;
-        if (key[e] > T) {
+        const unsigned long long mg = __builtin_amdgcn_ballot_w64(key[e] > T);
+        const unsigned long long me = __builtin_amdgcn_ballot_w64(key[e] == T);
+        if (lane == 0) {
+            const int wd = (e * kSelThreads + wave * 64) >> 5;
+            gt_words[wd] = (uint32_t)mg; gt_words[wd + 1] = (uint32_t)(mg >> 32);
+            eq_words[wd] = (uint32_t)me; eq_words[wd + 1] = (uint32_t)(me >> 32);
+        }
+    }
+    __syncthreads();
+    // thread t now owns tokens [32t, 32t + 32): ascending output slots through one block-wide exclusive scan
+    uint32_t mg = 0, me = 0;
+    if (tid < EPT * (kSelThreads / 32)) { mg = gt_words[tid]; me = eq_words[tid]; }
+    int gt_before, eq_before;
+    block_exscan2(__builtin_popcount(mg), __builtin_popcount(me), slots + 2 * kSelWaves, gt_before, eq_before);
+    // Kept indices are gathered in LDS at their output slots and then written out in one coalesced sweep; written
+    // straight from here, every store of a wave would touch 64 different cache lines.
+    uint32_t m = mg | me;
+    while (m) {
+        const int bpos = __builtin_ctz(m);
+        m &= m - 1;
+        const int j = tid * 32 + bpos;
+        if ((mg >> bpos) & 1u) {
             lds_out[gt_before + min(eq_before, need_eq)] = j;
             ++gt_before;
-        } else if (key[e] == T) {
+        } else {
             if (eq_before < need_eq) lds_out[gt_before + eq_before] = j;
             ++eq_before;
         }
@@ -162,7 +219,7 @@ hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budg
 #define AUDIOKV_LAUNCH_SELECT(E)                                                                        \
     do {                                                                                                \
         const size_t n = (size_t)(E) * kSelThreads;                                                     \
-        const size_t smem = (n + n / 32 + 1) * sizeof(float);                                           \
+        const size_t smem = n * sizeof(int32_t);                                                        \
         static bool attr_set = false;                                                                   \
         if (!attr_set && smem > 48 * 1024) {                                                            \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<E>),         \
