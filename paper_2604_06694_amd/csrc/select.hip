@@ -61,7 +61,7 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int* slots /* 2*kSel
     eb = pb + ib - b;
 }
 
-constexpr int kCompact = 4;          // undecided keys per thread once the candidates have been narrowed down
+constexpr int kCompact = 8;          // undecided keys per thread once the candidates have been narrowed down
 
 template <int EPT>   // tokens per thread; the head must have at most EPT * kSelThreads candidates
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
@@ -71,8 +71,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     extern __shared__ int32_t lds_out[];             // kept indices at their output slots (up to EPT*kSelThreads)
     __shared__ int slots[4 * kSelWaves];
     __shared__ int pass_count[3];
-    __shared__ uint32_t narrowed[kCompact * kSelThreads];               // keys still undecided after narrowing
     __shared__ uint32_t gt_words[kSelThreads + 2], eq_words[kSelThreads + 2];   // one bit per token, 32 tokens per word
+    // keys still undecided after narrowing: in the output buffer, which is not needed before the threshold is known
+    uint32_t* narrowed = reinterpret_cast<uint32_t*>(lds_out);
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
@@ -131,10 +132,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     bool narrow = false;
     for (; bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
-        // wave-wide count on the scalar unit: one compare per key, its lane mask counted with a population count
+        // Wave-wide count, split between the two issue ports so that neither is the bottleneck: the even registers
+        // through lane masks and population counts on the scalar unit (which the whole CU shares), the odd ones
+        // through a per-lane counter on the vector unit, whose bits are then summed with a few lane masks.
         int c = 0;
+        uint32_t per_lane = 0;
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= trial));
+        for (int e = 0; e < EPT; ++e) {
+            if (e & 1) per_lane += key[e] >= trial ? 1u : 0u;
+            else c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= trial));
+        }
+#pragma unroll
+        for (int bb = 0; (EPT / 2) >> bb; ++bb)      // per_lane <= EPT / 2
+            c += __builtin_popcountll(__builtin_amdgcn_ballot_w64((per_lane >> bb) & 1u)) << bb;
         decide(trial, c, 0);
         // Few undecided keys left (uniform decision)? T >> bit != 0 keeps the padding key 0 out of the bracket.
         if (EPT > kCompact && bit > 0 && (T >> bit) != 0u && c_lo - c_up <= kCompact * kSelThreads) { narrow = true; break; }
