@@ -52,11 +52,16 @@ template <int K>
 __device__ __forceinline__ void pooled_pair_lds(const float* x, int L, int j0, int mode, float& o0, float& o1) {
     const float fill = mode == AUDIOKV_POOL_AVG ? 0.f : -INFINITY;
     float w[K + 1];
+    if (j0 - K / 2 >= 0 && j0 + 1 + K / 2 < L) {     // every tap inside the sequence: all but the edge threads
 #pragma unroll
-    for (int u = 0; u <= K; ++u) {
-        const int p = j0 - K / 2 + u;
-        const float v = x[min(max(p, 0), L - 1)];
-        w[u] = (p >= 0 && p < L) ? v : fill;
+        for (int u = 0; u <= K; ++u) w[u] = x[j0 - K / 2 + u];
+    } else {
+#pragma unroll
+        for (int u = 0; u <= K; ++u) {
+            const int p = j0 - K / 2 + u;
+            const float v = x[min(max(p, 0), L - 1)];
+            w[u] = (p >= 0 && p < L) ? v : fill;
+        }
     }
     if (mode == AUDIOKV_POOL_AVG) {
         float a0 = 0.f, a1 = 0.f;
