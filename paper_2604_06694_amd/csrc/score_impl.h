@@ -15,9 +15,12 @@
 // d*2 bytes of the key itself, so recomputing is the cheaper choice.
 //
 // Both sweeps are bound by the vector ALU next to the matrix pipe: each logit
-// costs one MFMA-lane-slot plus (fma, exp2, add). The 32x32x16 shape is used
-// because one MFMA issue then covers twice as many logits as 16x16x32, which
-// leaves more issue slots in which the vector work of the previous block hides.
+// costs one MFMA-lane-slot plus (fma, exp2, add); measured on gfx950 a plain
+// vector op takes 4 issue cycles of a SIMD, an exp2 about 8.5, an MFMA issue
+// about 8 (its 32 cycles on the matrix pipe run beside the vector work). The
+// 32x32x16 shape is used because one MFMA issue then covers twice as many
+// logits as 16x16x32, which leaves more issue slots in which the vector work
+// of the previous block hides.
 //
 // Tiling. A workgroup of WR compute waves plus one loader wave owns one KV head
 // and a range of key tiles. The window queries are the stationary MFMA operand:
@@ -256,17 +259,14 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     // --- reduction of one block, cut into KK slices -------------------------------------------------------------
     float red_c[NB];                                    // sweep 1: base-2 reference of the block in flight
     float red_s[2];                                     // partial sums (two chains)
-    f32x4 red_rc[2][NB];                                // sweep 2: row constants of 4 rows, loaded one group ahead
-    // rows 8*q4 + 4*g2 + {0..3} of every row tile: one 16-byte LDS read serves four result elements
-    auto rc_load = [&](int q4) {
-#pragma unroll
-        for (int rb = 0; rb < NB; ++rb)
-            red_rc[q4 & 1][rb] = *reinterpret_cast<const f32x4*>(lds_rc + row0 + g2 * 4 + rb * 32 + q4 * 8);
-    };
+    // sweep 2: a lane always meets the same 16 rows of a row tile (c_row(i, g2)), so their constants stay in registers
+    float rcv[NB][16];
+    // The scale is read through this copy. The empty asm statements in run_block take it as an in/out operand, which
+    // ties every slice of vector work to its place between two MFMAs (see there).
+    float c_pin = c;
     auto reduce_begin = [&](auto masked_tag, f32x16 (&a)[NB], int j0b) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         red_s[0] = red_s[1] = 0.f;
-        if (SWEEP2) rc_load(0);
         if (!SWEEP2) {
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
@@ -293,29 +293,31 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                     if (j0b + l32 > last_visible(g, L, R, rowg0 + rb * 32 + c_row(i, g2))) a[rb][i] = -INFINITY;
         }
     };
-    auto reduce_slice = [&](f32x16 (&a)[NB], int sl) {  // elements [sl*SLICE, (sl+1)*SLICE) of every row tile
+    auto reduce_part = [&](f32x16 (&a)[NB], int sl, int rb) {  // elements [sl*SLICE, (sl+1)*SLICE) of row tile rb
 #pragma unroll
         for (int e = 0; e < SLICE; ++e) {
             const int i = sl * SLICE + e;
-            // the constants of the next four elements are requested a group ahead of their use, so that the
-            // wait for them never drains the K fragments that were prefetched behind them
-            if (SWEEP2 && (i & 3) == 0 && i + 4 < 16) rc_load((i >> 2) + 1);
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                if (SWEEP2) {
-                    red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_rc[(i >> 2) & 1][rb][i & 3]));
-                } else {
-                    if (rb == 0) red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
-                    else         run_l[rb] += fast_exp2(fmaf(a[rb][i], c, -red_c[rb]));
-                }
+            if (SWEEP2) {
+                red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c_pin, -rcv[rb][i]));
+            } else {
+                if (rb == 0) red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c_pin, -red_c[rb]));
+                else         run_l[rb] += fast_exp2(fmaf(a[rb][i], c_pin, -red_c[rb]));
             }
         }
     };
     auto reduce_end = [&](int cbuf, int kb) {
         if (SWEEP2) {
             // rows held by the other half of the wave; the other waves' rows are added by the loader wave
+            // v_permlane32_swap trades lanes 32..63 of its first operand with lanes 0..31 of its second: afterwards
+            // one register holds the lower-half sums in both halves, the other the upper-half sums. (Written as asm
+            // because the two-result builtin got its results merged; the wait states in front cover the vector
+            // write that produces the operands.)
             float v = red_s[0] + red_s[1];
-            v += __shfl_xor(v, 32, 64);
+#if defined(__HIP_DEVICE_COMPILE__)
+            float v_hi = v;
+            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(v), "+v"(v_hi));
+            v += v_hi;
+#endif
             if (g2 == 0) lds_cols[cbuf * (WR * T::TK) + wave * T::TK + kb * 32 + l32] = v;
         } else {
             run_l[0] += red_s[0] + red_s[1];
@@ -339,8 +341,10 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
             if (DO_MFMA) {
                 if (kk + PF < T::KK) frag_load(slot_m, kb_m, kk + PF, (kk + PF) % RING);
                 else if (STREAM)     frag_load(slot_n, kb_n, kk + PF - T::KK, (kk + PF) % RING);
+            }
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb) {
+            for (int rb = 0; rb < NB; ++rb) {
+                if (DO_MFMA) {
                     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                     const f32x16 cin = (kk == 0) ? zero : am[rb];
                     if (SWEEP2)   // C[row][key]: lane = key l32, rows c_row(i, g2)
@@ -348,9 +352,20 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                     else          // C[key][row]: lane = row l32, keys c_row(i, g2)
                         am[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk % RING], qf[rb][kk], cin, 0, 0, 0);
                 }
+                if (DO_RED && kk < 16) reduce_part(ar, kk, rb);
+                // One MFMA, then SLICE logits of vector work (about as long as the MFMA occupies the matrix pipe),
+                // then the next MFMA: a wave issues in order, so two MFMAs back to back would hold its vector work
+                // up for a whole pass of the matrix pipe. The arithmetic has no side effects, and the compiler would
+                // otherwise gather all MFMAs of the block in front of all the vector work; an empty asm statement
+                // that takes the accumulator, the sums and the scale in and out fixes the order.
+#if defined(__HIP_DEVICE_COMPILE__)
+                if (DO_MFMA && DO_RED) {
+                    if constexpr (NB == 1)      asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]));
+                    else if constexpr (NB == 2) asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(run_l[1]));
+                    else                        asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(run_l[1]), "+v"(run_l[NB - 1]));
+                }
+#endif
             }
-            if (DO_RED && kk < 16) reduce_slice(ar, kk);
-            // keep each k-step together: one MFMA per row tile with its slice of vector work behind it
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -362,7 +377,17 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     const int t_plain_end = min(max(t_first_masked, t_begin), t_end);
     auto slot_of = [&](int t) { return (t - t_begin) % T::STAGES; };
 
-    __syncthreads();                                    // the first tiles are in the ring
+    __syncthreads();                                    // the first tiles are in the ring (and lds_rc is filled)
+    if (SWEEP2) {
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(lds_rc + row0 + g2 * 4 + rb * 32 + q4 * 8);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) rcv[rb][q4 * 4 + u] = v[u];
+            }
+    }
     int t = t_begin;
     if (t < t_plain_end) {
         // ---- pipelined part: blocks (t, 0), (t, 1), (t + 1, 0), ... ; acc0 holds even blocks, acc1 odd ones
