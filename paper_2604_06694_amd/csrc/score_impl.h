@@ -77,11 +77,11 @@ struct Tile {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// (m, l) <- merge of two partial softmax statistics in raw-logit units (c > 0 converts to base 2)
-__device__ __forceinline__ void merge_stats(float& m, float& l, float m2, float l2, float c) {
+// (m, l) <- merge of two partial softmax statistics (m in base-2 units)
+__device__ __forceinline__ void merge_stats(float& m, float& l, float m2, float l2) {
     const float M = fmaxf(m, m2);
     const float Ms = (M == -INFINITY) ? 0.f : M;
-    l = l * fast_exp2((m - Ms) * c) + l2 * fast_exp2((m2 - Ms) * c);
+    l = l * fast_exp2(m - Ms) + l2 * fast_exp2(m2 - Ms);
     m = M;
 }
 
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         for (int r = tid; r < T::ROWS; r += 64 * WR)
             lds_rc[r] = row_base + r < rows_pad ? cst[(size_t)head * rows_pad + row_base + r] : INFINITY;
 
-    // sweep 1: running max (raw logit units) and sum for row row0 + rb*32 + l32 over this lane's keys
+    // sweep 1: running max (base-2 units: logit * c) and sum for row row0 + rb*32 + l32 over this lane's keys
     float run_m[NB], run_l[NB];
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) { run_m[rb] = -INFINITY; run_l[rb] = 0.f; }
@@ -289,10 +289,12 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                 float mx = a[rb][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
-                const float m_new = fmaxf(run_m[rb], mx);
-                const float ms = (m_new == -INFINITY) ? 0.f : m_new;
-                red_c[rb] = ms * c;
-                run_l[rb] *= fast_exp2((run_m[rb] - ms) * c);
+                // c > 0, so the scaled maximum is the maximum of the scaled logits. Outside the masked tiles every
+                // logit is finite, and a reference of -inf (nothing seen yet) cannot survive the max.
+                const float m_new = fmaxf(run_m[rb], mx * c);
+                const float ms = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+                red_c[rb] = ms;
+                run_l[rb] *= fast_exp2(run_m[rb] - ms);
                 run_m[rb] = m_new;
             }
         } else if (MASKED) {
@@ -470,10 +472,10 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) {
             const float m2 = __shfl_xor(run_m[rb], 32, 64), l2 = __shfl_xor(run_l[rb], 32, 64);
-            merge_stats(run_m[rb], run_l[rb], m2, l2, c);
+            merge_stats(run_m[rb], run_l[rb], m2, l2);
             if (g2 == 0) {
                 const int r = rowg0 + rb * 32 + l32;
-                my_stats[2 * r] = (run_m[rb] == -INFINITY) ? -INFINITY : run_m[rb] * c;
+                my_stats[2 * r] = run_m[rb];
                 my_stats[2 * r + 1] = run_l[rb];
             }
         }
