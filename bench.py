@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: 28 layers x L=32768, W=64)")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--cutoff", type=float, default=None)
+    ap.add_argument("--seqlen", type=int, default=None,
+                    help="replace the sequence length of a fixed-length workload (e.g. 30000: a length that is not a power of two)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-layer", action="store_true", help="skip the one-launch-per-layer timing")
     ap.add_argument("--no-lse", action="store_true", help="skip the timing of the variant that is given the window's log-sum-exp")
@@ -125,6 +127,8 @@ def main():
         over["ratio"] = args.ratio
     if args.cutoff is not None:
         over["cutoff"] = args.cutoff
+    if args.seqlen is not None:
+        over["seqlen"] = args.seqlen
     cfg = get_config(args.config, **over)
     lens = [int(x) for x in gen_lengths(cfg)]
     dev = torch.device("cuda:0")
@@ -204,7 +208,7 @@ def main():
         roof = {"bound": "hbm", "achieved": ab[key] / dom_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    if args.ratio is None and args.cutoff is None:
+    if args.ratio is None and args.cutoff is None and args.seqlen is None:
         roof["traffic"] = measured_traffic(cfg.name).get(dominant)
 
     res = {

@@ -237,9 +237,9 @@ int32_t audiokv_compact(const audiokv_params* params,
  * library (created on first use, default priority) and joined back into
  * `stream` with events before the selection; everything is ordered after prior work on
  * `stream` and before later work on it. Calls on different streams may be in
- * flight together (separate workspaces and outputs), but because the helper
- * stream and its two events are shared, audiokv_evict must not be called from
- * several host threads at once. */
+ * flight together (separate workspaces and outputs), also from several host
+ * threads: the helper stream and its two events are shared, so the part of a
+ * call between the fork and the join holds a lock. */
 int32_t audiokv_evict(const audiokv_params* params,
                       const void* q_win, const void* k, const void* v,
                       const float* weights_dev, int32_t alloc_scope,

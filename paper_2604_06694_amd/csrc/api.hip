@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
@@ -184,9 +185,10 @@ struct Profile {
 struct Helper {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    std::mutex mu;      // one fork ... join sequence at a time: the stream and the two events are shared by all callers
 } g_helper;
 
-hipError_t ensure_helper() {
+hipError_t ensure_helper() {        // called with g_helper.mu held
     if (g_helper.stream) return hipSuccess;
     hipError_t e = hipStreamCreateWithFlags(&g_helper.stream, hipStreamNonBlocking);   // default priority
     if (e == hipSuccess) e = hipEventCreateWithFlags(&g_helper.fork, hipEventDisableTiming);
@@ -454,6 +456,8 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     const bool prof = g_prof.enabled && g_prof.created;
     // a small pool is allocated faster than a fork and a join are issued (55 us of host time): keep it in line then
     const bool side = !prof && hps >= 32;
+    std::unique_lock<std::mutex> helper_lock(g_helper.mu, std::defer_lock);
+    if (side) helper_lock.lock();
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
     AUDIOKV_MARK(0);
     if (!side) {
@@ -477,7 +481,10 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
                               alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");
     AUDIOKV_MARK(3);
-    if (side) AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
+    if (side) {
+        AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
+        helper_lock.unlock();
+    }
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
     AUDIOKV_MARK(4);

@@ -41,6 +41,7 @@
 // Everything is in base-2 units: z2 = <q,k> * scale * log2(e).
 #pragma once
 
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -553,7 +554,7 @@ hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void*
     using T = Tile<D, NB, WR>;
     const int n_heads = g.n_items * g.H_kv;
     const dim3 grid((unsigned)(n_heads * nsplit));
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     if (!attr_set && T::LDS_BYTES > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_kernel<D, NB, WR, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);

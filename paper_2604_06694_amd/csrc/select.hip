@@ -11,6 +11,7 @@
 // consecutive tokens back, and kept indices are written in ascending order
 // through a block-wide exclusive scan (gathered in LDS, stored coalesced).
 // Integer-only: bit-exact.
+#include <atomic>
 #include "common.h"
 
 namespace audiokv {
@@ -230,7 +231,7 @@ hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budg
     do {                                                                                                \
         const size_t n = (size_t)(E) * kSelThreads;                                                     \
         const size_t smem = n * sizeof(int32_t);                                                        \
-        static bool attr_set = false;                                                                   \
+        static std::atomic<bool> attr_set{false};                                                                   \
         if (!attr_set && smem > 48 * 1024) {                                                            \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<E>),         \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);  \

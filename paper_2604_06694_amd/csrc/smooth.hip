@@ -19,6 +19,7 @@
 // (everything above is masked), so the convolutions have L + K - 1 significant points and the transform size is
 // M >= L + K - 1 rather than 2L - 1: half the size for most lengths at the usual cutoffs. Stages whose span
 // exceeds the LDS (M > 16384) run on global memory, the rest on 16384-point chunks inside LDS.
+#include <atomic>
 #include "common.h"
 
 namespace audiokv {
@@ -1081,7 +1082,7 @@ SmoothPlan plan_smooth(const Geom& g, const int32_t* seqlens_host, int n_items, 
 }
 
 hipError_t smooth_kernel_attributes() {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     if (attr_set) return hipSuccess;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(smooth_pow2_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

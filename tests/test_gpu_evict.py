@@ -195,3 +195,42 @@ def test_error_paths_return_codes_without_enqueueing(A):
         A.score(bad, q, k, lens)
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+def test_evict_from_two_host_threads_matches_one(A):
+    """A pool of 32 heads or more sends the allocation to the library's helper stream; its fork and join are shared by
+    all callers. Two host threads, each on a stream of its own with its own outputs and workspace, must get what a
+    single thread gets (the path is deterministic: bit for bit)."""
+    import threading
+    cfg = get_config(2, n_items=8, seqlen=1536)            # 8 items x 4 KV heads = one global pool of 32 heads
+    items, lens, q, k, v, w = make_batch(cfg)
+    p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window, pool_kernel=cfg.pool_kernel,
+                 floor_frac=cfg.floor_frac)
+    wt = torch.from_numpy(w).cuda()
+    ref = A.evict(p, q, k, v, wt, lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=1)
+    torch.cuda.synchronize()
+    want = {n: ref[n].clone() for n in ("indices", "budgets", "cu_budgets", "k_out", "v_out")}
+    results, errors = {}, []
+
+    def worker(tid):
+        try:
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                out = None
+                for _ in range(6):
+                    out = A.evict(p, q, k, v, wt, lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=1,
+                                  outputs=out if out is None else {n: out[n] for n in want}, workspace=None if out is None else out["workspace"])
+            s.synchronize()
+            results[tid] = out
+        except Exception as e:                              # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for tid in range(2):
+        for n, x in want.items():
+            assert torch.equal(results[tid][n], x), (tid, n)
