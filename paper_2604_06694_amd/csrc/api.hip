@@ -456,6 +456,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     const bool prof = g_prof.enabled && g_prof.created;
     // a small pool is allocated faster than a fork and a join are issued (55 us of host time): keep it in line then
     const bool side = !prof && hps >= 32;
+    const bool side_filters = side && alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0;
     std::unique_lock<std::mutex> helper_lock(g_helper.mu, std::defer_lock);
     if (side) helper_lock.lock();
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
@@ -470,6 +471,11 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
         AUDIOKV_HIP(hipStreamWaitEvent(g_helper.stream, g_helper.fork, 0), "hipStreamWaitEvent");
         AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
                                     budgets_dev, cu_budgets_dev, g_helper.stream), "allocate kernel");
+        // the chirp tables and filter spectra of lengths that are not powers of two depend on the lengths and the
+        // cutoff only: half a dozen small kernels that also fit under the score sweeps
+        if (side_filters)
+            AUDIOKV_HIP(launch_smooth_filters(g, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, ws + w.fft_off,
+                                              g_helper.stream), "chirp-z filter kernels");
         AUDIOKV_HIP(hipEventRecord(g_helper.join, g_helper.stream), "hipEventRecord");
     }
     AUDIOKV_MARK(1);
@@ -478,13 +484,14 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
                              w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
                              (size_t)b.total_tokens * params->n_kv_heads), "score kernels");
     AUDIOKV_MARK(2);
-    AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
-                              alpha, smoothed, ws + w.fft_off, nullptr, false, s), "smooth kernel");
-    AUDIOKV_MARK(3);
     if (side) {
-        AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");   // budgets are ready
+        // budgets (needed by select) and filters (needed by smooth) are ready; by now the helper's work is long done
+        AUDIOKV_HIP(hipStreamWaitEvent(s, g_helper.join, 0), "hipStreamWaitEvent");
         helper_lock.unlock();
     }
+    AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
+                              alpha, smoothed, ws + w.fft_off, nullptr, false, s, side_filters), "smooth kernel");
+    AUDIOKV_MARK(3);
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");
     AUDIOKV_MARK(4);
