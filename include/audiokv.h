@@ -25,6 +25,8 @@
  *   without synchronising. Inputs, outputs and workspace must stay alive, and
  *   the workspace must not be shared with a concurrent call, until the stream
  *   has drained. On a validation error nothing is enqueued.
+ * - An empty batch (n_items = 0) is accepted by every entry point: the call
+ *   returns AUDIOKV_OK and enqueues nothing (sizes come back as 0).
  * - Deterministic: equal inputs give bit-identical outputs.
  *
  * Batch layout

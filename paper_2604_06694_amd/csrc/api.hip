@@ -224,9 +224,10 @@ int32_t audiokv_total_kept(const audiokv_params* params, int32_t n_items, const 
                            double ratio, int64_t* out_rows)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (!out_rows) return fail(AUDIOKV_E_INVALID_ARG, "out_rows is NULL");
+    if (n_items == 0) { *out_rows = 0; return AUDIOKV_OK; }
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
-    if (!out_rows) return fail(AUDIOKV_E_INVALID_ARG, "out_rows is NULL");
     AUDIOKV_TRY(check_ratio(params, b, seqlens_host, ratio));
     int64_t tot = 0;
     for (int i = 0; i < n_items; ++i) tot += (int64_t)audiokv_n_keep(ratio, seqlens_host[i]) * params->n_kv_heads;
@@ -238,9 +239,10 @@ int32_t audiokv_workspace_bytes(const audiokv_params* params, int32_t n_items, c
                                 size_t* out_bytes)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (!out_bytes) return fail(AUDIOKV_E_INVALID_ARG, "out_bytes is NULL");
+    if (n_items == 0) { *out_bytes = 0; return AUDIOKV_OK; }
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
-    if (!out_bytes) return fail(AUDIOKV_E_INVALID_ARG, "out_bytes is NULL");
     *out_bytes = plan_workspace(params, b, seqlens_host).total;
     return AUDIOKV_OK;
 }
@@ -251,6 +253,7 @@ int32_t score_entry(const audiokv_params* params, const void* q_win, const void*
                     float* scores, void* workspace, size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 1));
+    if (n_items == 0) return AUDIOKV_OK;           // an empty batch: nothing to enqueue
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
     if (!q_win || !k || !cu_seqlens_dev || !scores || !workspace)
@@ -286,7 +289,7 @@ int32_t audiokv_score_lse(const audiokv_params* params, const void* q_win, const
                           const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
                           float* scores, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!lse_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_score_lse: NULL lse_dev");
+    if (!lse_dev && n_items != 0) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_score_lse: NULL lse_dev");
     return score_entry(params, q_win, k, lse_dev, cu_seqlens_dev, seqlens_host, n_items, scores, workspace,
                        workspace_bytes, stream);
 }
@@ -297,6 +300,7 @@ int32_t audiokv_allocate(const audiokv_params* params, const float* weights_dev,
                          int32_t* cu_budgets_dev, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (n_segments == 0) return AUDIOKV_OK;
     if (n_segments < 1 || heads_per_segment < 1 || weight_group < 1)
         return fail(AUDIOKV_E_INVALID_ARG, "n_segments, heads_per_segment and weight_group must be >= 1");
     if (heads_per_segment > 1536)
@@ -330,6 +334,7 @@ int32_t smooth_entry(const audiokv_params* params, const float* scores_in, const
                      size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (n_items == 0) return AUDIOKV_OK;
     audiokv_params p2 = *params;
     p2.window = 0;                                // lengths are not tied to the window here
     Batch b;
@@ -377,6 +382,7 @@ int32_t audiokv_select(const audiokv_params* params, const float* scores, const 
 {
     (void)workspace; (void)workspace_bytes;
     AUDIOKV_TRY(check_params(params, 0));
+    if (n_items == 0) return AUDIOKV_OK;
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
     if (!scores || !budgets_dev || !cu_budgets_dev || !cu_seqlens_dev || !indices_dev)
@@ -395,6 +401,7 @@ int32_t audiokv_compact(const audiokv_params* params, const void* k, const void*
                         int32_t n_items, int64_t total_rows, void* k_out, void* v_out, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (n_items == 0) return AUDIOKV_OK;
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
     if (!k || !v || !indices_dev || !cu_budgets_dev || !cu_seqlens_dev || !k_out || !v_out)
@@ -419,6 +426,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
                     void* workspace, size_t workspace_bytes, void* stream)
 {
     AUDIOKV_TRY(check_params(params, 1));
+    if (n_items == 0) return AUDIOKV_OK;
     Batch b;
     AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
     if (!q_win || !k || !v || !weights_dev || !cu_seqlens_dev || !k_out || !v_out || !indices_dev || !budgets_dev ||
@@ -522,7 +530,7 @@ int32_t audiokv_evict_lse(const audiokv_params* params, const void* q_win, const
                           void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev,
                           int32_t* cu_budgets_dev, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!lse_dev) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_evict_lse: NULL lse_dev");
+    if (!lse_dev && n_items != 0) return fail(AUDIOKV_E_INVALID_ARG, "audiokv_evict_lse: NULL lse_dev");
     return evict_entry(params, q_win, k, v, lse_dev, weights_dev, alloc_scope, cu_seqlens_dev, seqlens_host, n_items,
                        ratio, cutoff_frac, alpha, k_out, v_out, indices_dev, budgets_dev, cu_budgets_dev, workspace,
                        workspace_bytes, stream);
@@ -532,8 +540,9 @@ int32_t audiokv_decode_workspace_bytes(const audiokv_params* params, int32_t n_i
                                        size_t* out_bytes)
 {
     AUDIOKV_TRY(check_params(params, 0));
-    if (!out_bytes || n_items < 1 || total_rows < 0 || total_rows > (int64_t)INT32_MAX)
-        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_decode_workspace_bytes: NULL pointer, n_items < 1 or total_rows out of range");
+    if (!out_bytes || n_items < 0 || total_rows < 0 || total_rows > (int64_t)INT32_MAX)
+        return fail(AUDIOKV_E_INVALID_ARG, "audiokv_decode_workspace_bytes: NULL pointer, n_items < 0 or total_rows out of range");
+    if (n_items == 0) { *out_bytes = 0; return AUDIOKV_OK; }
     *out_bytes = decode_workspace_bytes(make_geom(params, n_items), total_rows);
     return AUDIOKV_OK;
 }
@@ -544,6 +553,7 @@ int32_t audiokv_decode_attend(const audiokv_params* params, const void* q_dev, c
                               void* stream)
 {
     AUDIOKV_TRY(check_params(params, 0));
+    if (n_items == 0) return AUDIOKV_OK;
     if (!q_dev || !k_cache || !v_cache || !cu_budgets_dev || !out_dev || !workspace)
         return fail(AUDIOKV_E_INVALID_ARG, "audiokv_decode_attend: NULL pointer argument");
     if (n_items < 1 || total_rows < 0 || total_rows > (int64_t)INT32_MAX)

@@ -75,9 +75,6 @@ def test_validation_errors_are_codes_not_crashes(A):
     with pytest.raises(A.AudioKVError) as e:
         A.total_kept(good, [16], 0.5)             # L below the window
     assert e.value.code == -1
-    with pytest.raises(A.AudioKVError) as e:
-        A.total_kept(good, [], 0.5)
-    assert e.value.code == -1
     # a GPU entry point given NULL pointers returns before touching the device
     lib = A.binding._lib
     cp = good.c()
@@ -91,3 +88,28 @@ def test_validation_errors_are_codes_not_crashes(A):
     bad.size = 12
     rc = lib.audiokv_score(C.byref(bad), None, None, None, lens, 1, None, None, 0, None)
     assert rc == -1 and b"size" in lib.audiokv_last_error()
+
+
+def test_empty_batch_is_accepted_everywhere_and_enqueues_nothing(A):
+    """n_items = 0: every entry point returns AUDIOKV_OK before looking at any pointer (so this runs without a GPU);
+    sizes come back as 0. Invalid params are still refused."""
+    p = A.Params(28, 4, 128, 32)
+    assert A.total_kept(p, [], 0.4) == 0
+    assert A.workspace_bytes(p, []) == 0
+    lib = A.binding._lib
+    cp = p.c()
+    assert lib.audiokv_score(C.byref(cp), None, None, None, None, 0, None, None, 0, None) == 0
+    assert lib.audiokv_score_lse(C.byref(cp), None, None, None, None, None, 0, None, None, 0, None) == 0
+    assert lib.audiokv_allocate(C.byref(cp), None, 0, 4, 1, None, None, C.c_double(0.4), None, None, None) == 0
+    assert lib.audiokv_smooth(C.byref(cp), None, None, None, 0, C.c_double(0.125), C.c_double(1.0), None, None, 0, None) == 0
+    assert lib.audiokv_smooth_cutoffs(C.byref(cp), None, None, None, 0, C.c_double(0.9), None, None, 0, None) == 0
+    assert lib.audiokv_select(C.byref(cp), None, None, None, None, None, 0, None, None, 0, None) == 0
+    assert lib.audiokv_compact(C.byref(cp), None, None, None, None, None, None, 0, C.c_int64(0), None, None, None) == 0
+    assert lib.audiokv_evict(C.byref(cp), None, None, None, None, 1, None, None, 0, C.c_double(0.4), C.c_double(0.125),
+                             C.c_double(1.0), None, None, None, None, None, None, 0, None) == 0
+    out = C.c_size_t(7)
+    assert lib.audiokv_decode_workspace_bytes(C.byref(cp), 0, C.c_int64(0), C.byref(out)) == 0 and out.value == 0
+    assert lib.audiokv_decode_attend(C.byref(cp), None, None, None, None, 0, C.c_int64(0), None, None, 0, None) == 0
+    bad = A.Params(28, 5, 128, 32).c()
+    assert lib.audiokv_evict(C.byref(bad), None, None, None, None, 1, None, None, 0, C.c_double(0.4), C.c_double(0.125),
+                             C.c_double(1.0), None, None, None, None, None, None, 0, None) == -1

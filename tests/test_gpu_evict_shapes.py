@@ -114,3 +114,14 @@ def test_evict_degenerate_budgets(A, L, W, ratio):
             s_hat = O.smooth(s[h], 0.25, 1.0)
             thr = np.sort(s_hat[:L - W])[::-1][int(b[h]) - W - 1]
             assert np.all(np.abs(s_hat[diff] - thr) <= SCORE_RTOL * np.abs(s_hat).max())
+
+
+def test_empty_batch_through_the_binding(A):
+    """No items: the fused call and the stage calls return without enqueueing anything."""
+    p = A.Params(8, 2, 128, 16)
+    e16 = torch.empty(0, dtype=torch.bfloat16, device="cuda")
+    out = A.evict(p, e16, e16, e16, torch.empty(0, dtype=torch.float32, device="cuda"), [], 0.4, 0.125, 1.0)
+    assert out["total_rows"] == 0
+    s = A.score(p, e16, e16, [])
+    assert s.numel() == 0
+    torch.cuda.synchronize()
