@@ -186,7 +186,9 @@ int32_t audiokv_allocate(const audiokv_params* params,
  *                            fp32 squares accumulated in float64;
  *   AUDIOKV_CUTOFF_ENERGY_NO_DC  the same with both sums starting at bin 1.
  * alpha in [0,1] (0: bitwise copy). scores_out may alias scores_in. fp32
- * arithmetic with float64-generated twiddles. */
+ * arithmetic with float64-generated twiddles. Lengths up to 131072 (longer:
+ * AUDIOKV_E_UNSUPPORTED unless alpha = 0); lengths that are not powers of two,
+ * and all lengths above 32768, need the workspace. */
 int32_t audiokv_smooth(const audiokv_params* params,
                        const float* scores_in,
                        const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,

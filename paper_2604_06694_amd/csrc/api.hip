@@ -160,7 +160,7 @@ int32_t check_smooth_lengths(const Batch& b, const int32_t* seqlens_host, double
     for (int i = 0; i < b.n_items; ++i)
         if (!smooth_supported(seqlens_host[i]))
             return fail(AUDIOKV_E_UNSUPPORTED, "item %d: spectral smoothing of length %d is not built "
-                        "(lengths up to 32768)", i, seqlens_host[i]);
+                        "(lengths up to 131072)", i, seqlens_host[i]);
     return AUDIOKV_OK;
 }
 

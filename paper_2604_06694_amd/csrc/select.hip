@@ -218,9 +218,85 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     for (int t = tid; t < want; t += kSelThreads) out[t] = lds_out[t];
 }
 
+// Heads longer than 32 * 1024 tokens: the keys do not fit the registers of one workgroup, so every counting pass
+// streams the scores again (they stay in L2: 4 bytes per token), and the output pass walks the sequence in rounds of
+// 32 consecutive tokens per thread. Same threshold, same tie rule, same ascending order; slower per token than the
+// register kernel (32 full passes), meant for the rare very long head.
+__global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
+    Geom g, const float* __restrict__ scores, const int32_t* __restrict__ budgets,
+    const int32_t* __restrict__ cu_b, const int32_t* __restrict__ cu_seq, int32_t* __restrict__ indices)
+{
+    __shared__ int slots[4 * kSelWaves];
+    const int head = blockIdx.x;
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    const int tok0 = cu_seq[item];
+    const int L = cu_seq[item + 1] - tok0;
+    const float* s = scores + (size_t)tok0 * g.H_kv + (size_t)h * L;
+    const int tid = threadIdx.x;
+
+    const int W = min(g.W, L);
+    const int n_cand = L - W;
+    const int room = cu_b[head + 1] - cu_b[head];
+    const int b = min(min(max(budgets[head], W), L), room);
+    const int want = max(b - W, 0);
+    int32_t* out = indices + cu_b[head];
+    for (int w = tid; w < W; w += kSelThreads)
+        if (want + w < room) out[want + w] = n_cand + w;
+    if (want <= 0) return;
+
+    // the largest T with #(key >= T) >= want, bit by bit; c_up ends as #(key > T): the count of the last trial that
+    // failed, which is T + 1 (all lower bits of T are ones from there down)
+    uint32_t T = 0;
+    int c_up = 0, parity = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        int c = 0;
+        for (int j = tid; j < n_cand; j += kSelThreads) c += order_key(s[j]) >= trial ? 1 : 0;
+        const int t = block_count(c, slots, parity);
+        parity ^= 1;
+        if (t >= want) T = trial; else c_up = t;
+    }
+    const int need_eq = want - c_up;
+
+    int gt_base = 0, eq_base = 0;                    // tokens > T and == T in the rounds before this one
+    for (int base = 0; base < n_cand; base += 32 * kSelThreads) {
+        const int j0 = base + tid * 32;
+        uint32_t mg = 0, me = 0;
+        for (int u = 0; u < 32; ++u) {
+            const int j = j0 + u;
+            if (j < n_cand) {
+                const uint32_t key = order_key(s[j]);
+                mg |= (key > T ? 1u : 0u) << u;
+                me |= (key == T ? 1u : 0u) << u;
+            }
+        }
+        int gt_before, eq_before;
+        block_exscan2(__builtin_popcount(mg), __builtin_popcount(me), slots + 2 * kSelWaves, gt_before, eq_before);
+        int gt_round = 0, eq_round = 0;
+        for (int w = 0; w < kSelWaves; ++w) { gt_round += slots[2 * kSelWaves + w]; eq_round += slots[3 * kSelWaves + w]; }
+        gt_before += gt_base;
+        eq_before += eq_base;
+        uint32_t m = mg | me;
+        while (m) {
+            const int bpos = __builtin_ctz(m);
+            m &= m - 1;
+            if ((mg >> bpos) & 1u) {
+                out[gt_before + min(eq_before, need_eq)] = j0 + bpos;
+                ++gt_before;
+            } else {
+                if (eq_before < need_eq) out[gt_before + eq_before] = j0 + bpos;
+                ++eq_before;
+            }
+        }
+        gt_base += gt_round;
+        eq_base += eq_round;
+        __syncthreads();                             // the scan slots are rewritten by the next round
+    }
+}
+
 }  // namespace
 
-bool select_supported(int L) { return L >= 1 && L <= 32 * kSelThreads; }
+bool select_supported(int L) { return L >= 1; }
 
 hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budgets, const int32_t* cu_budgets,
                          const int32_t* cu_seqlens, int max_L, int32_t* indices, hipStream_t s)
@@ -244,7 +320,9 @@ hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budg
     if (ept_needed <= 4) AUDIOKV_LAUNCH_SELECT(4);
     else if (ept_needed <= 16) AUDIOKV_LAUNCH_SELECT(16);
     else if (ept_needed <= 32) AUDIOKV_LAUNCH_SELECT(32);
-    else return hipErrorInvalidValue;   // longer heads would need more than the 160 KiB of LDS staging
+    else   // longer heads than the registers and the LDS staging of one workgroup hold
+        hipLaunchKernelGGL(select_stream_kernel, dim3(n_heads), dim3(kSelThreads), 0, s, g, scores, budgets, cu_budgets,
+                           cu_seqlens, indices);
 #undef AUDIOKV_LAUNCH_SELECT
     return hipGetLastError();
 }

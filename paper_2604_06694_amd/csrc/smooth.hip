@@ -445,8 +445,10 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
 // ------------------------ arbitrary length: Bluestein over global memory -----------------------
 
 constexpr int kChunkLog = 14;                     // 16384 complex = 128 KiB: the part of an FFT that fits in LDS
-constexpr int kWideMinLog = 12;                   // transforms of 4096 points and more are spread over four workgroups
-constexpr int kMaxBluesteinLog = 16;              // M <= 65536, i.e. L <= 32768
+constexpr int kWideMinLog = 12;                   // transforms of 4096 points and more are spread over four workgroups,
+constexpr int kWideMaxLog = 16;                   // up to the 65536 points that four LDS chunks hold
+constexpr int kMaxBluesteinLog = 18;              // M <= 262144: any L <= 131072 at any cutoff
+__host__ __device__ inline bool wide_size(int logM) { return logM >= kWideMinLog && logM <= kWideMaxLog; }
 
 // log2 of the transform size for L samples and K wanted bins: the smallest power of two >= L + K - 1
 __host__ __device__ inline int bluestein_log(int L, int K) {
@@ -549,6 +551,31 @@ __device__ __noinline__ void top_stages(cf* __restrict__ x, int logM, bool inver
             for (int r = 0; r < 4; ++r) st2(x, i + r * q, v[r][0], v[r][1]);
         }
         __syncthreads();
+    } else if (extra > 2) {
+        // very long heads (M > 65536): one plain radix-2 pass over global memory per top stage, half-sizes M/2,
+        // M/4, ... forwards and the reverse order backwards. Stage `sh` has half-size m = M >> (sh + 1): pair p sits
+        // in block p / m at offset p % m, and its twiddle is root_M^(offset * 2^sh).
+        for (int st = 0; st < extra; ++st) {
+            const int sh = inverse ? extra - 1 - st : st;
+            const int logm = logM - 1 - sh;
+            const int m = 1 << logm;
+            for (int p = 2 * tid; p < (M >> 1); p += 2 * kFftThreads) {     // m is even: p and p + 1 share a block
+                const int off = p & (m - 1);
+                const int i = ((p >> logm) << (logm + 1)) + off;
+                cf a[2], c[2];
+                ld2(x, i, a[0], a[1]);
+                ld2(x, i + m, c[0], c[1]);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const cf w = tw_m(lo, hi, (off + u) << sh);
+                    if (!inverse) { const cf d = csub(a[u], c[u]); a[u] = cadd(a[u], c[u]); c[u] = cmul(d, w); }
+                    else { const cf cw = cmul(c[u], cconj(w)); c[u] = csub(a[u], cw); a[u] = cadd(a[u], cw); }
+                }
+                st2(x, i, a[0], a[1]);
+                st2(x, i + m, c[0], c[1]);
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -648,7 +675,7 @@ __global__ __launch_bounds__(kFftThreads) void bluestein_prepare_kernel(const in
     const int tid = threadIdx.x;
     const int K = wanted_bins(L, cutoff_frac, cutoff_mode, taper_bins);
     const int logM = bluestein_log(L, K);
-    if (skip_wide && logM >= kWideMinLog) return;     // prepared by the multi-workgroup kernels
+    if (skip_wide && wide_size(logM)) return;         // prepared by the multi-workgroup kernels
     const int M = 1 << logM;
     const int C = M < (1 << kChunkLog) ? M : (1 << kChunkLog);
     cf* z = reinterpret_cast<cf*>(smem);
@@ -689,7 +716,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const int L = cu_seq[item + 1] - tok0;
     if (alpha == 0.f || pow2_length(L)) return;       // the LDS kernel owns this head
     // all but the small transforms are spread over several workgroups by the kernels below
-    if (skip_wide && bluestein_log(L, wanted_bins(L, cutoff_frac, g.cutoff_mode, g.taper_bins)) >= kWideMinLog) return;
+    if (skip_wide && wide_size(bluestein_log(L, wanted_bins(L, cutoff_frac, g.cutoff_mode, g.taper_bins)))) return;
     const size_t off = (size_t)tok0 * g.H_kv + (size_t)h * L;
     const float* src = in + off;
     float* dst = out + off;
@@ -796,7 +823,7 @@ __device__ __forceinline__ bool wide_head(const Geom& g, const int32_t* __restri
     if (pow2_length(w.L)) return false;
     w.K = wanted_bins(w.L, cutoff_frac, g.cutoff_mode, g.taper_bins);
     w.logM = bluestein_log(w.L, w.K);
-    if (w.logM < kWideMinLog) return false;            // small: the single-workgroup kernel owns it
+    if (!wide_size(w.logM)) return false;              // small or very large: the single-workgroup kernel owns it
     w.M = 1 << w.logM;
     w.extra = 2;                                       // two top stages, four chunks of M / 4 <= 16384 points
     w.R = 1 << w.extra;
@@ -1055,7 +1082,7 @@ hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlen
     return hipGetLastError();
 }
 
-bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && bluestein_log_max(L) <= kMaxBluesteinLog); }
+bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && L <= 131072 && bluestein_log_max(L) <= kMaxBluesteinLog); }
 
 size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
     // sized for the largest transform any cutoff can ask for (all bins wanted)
@@ -1069,14 +1096,17 @@ size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv
 }
 
 namespace {
-struct SmoothPlan { int max_pow2 = 0, max_log = 0; };
+struct SmoothPlan { int max_pow2 = 0, max_log = 0; bool any_wide = false; };
 
 SmoothPlan plan_smooth(const Geom& g, const int32_t* seqlens_host, int n_items, double cutoff_frac) {
     SmoothPlan p;
     for (int i = 0; i < n_items; ++i) {
         if (pow2_length(seqlens_host[i])) p.max_pow2 = max(p.max_pow2, seqlens_host[i]);
-        else p.max_log = max(p.max_log, bluestein_log(seqlens_host[i], wanted_bins(seqlens_host[i], cutoff_frac,
-                                                                                   g.cutoff_mode, g.taper_bins)));
+        else {
+            const int lg = bluestein_log(seqlens_host[i], wanted_bins(seqlens_host[i], cutoff_frac, g.cutoff_mode, g.taper_bins));
+            p.max_log = max(p.max_log, lg);
+            p.any_wide = p.any_wide || wide_size(lg);
+        }
     }
     return p;
 }
@@ -1116,7 +1146,7 @@ hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const
     if (e != hipSuccess) return e;
     const size_t M = (size_t)1 << pl.max_log;
     const BluesteinWs bw{static_cast<cf*>(workspace), M, g.n_items * g.H_kv};
-    const bool wide = pl.max_log >= kWideMinLog;
+    const bool wide = pl.any_wide;
     hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), bluestein_smem(g, M), s, cu_seqlens,
                        bw, cutoff_frac, g.cutoff_mode, g.taper_bins, wide ? 1 : 0);
     if (wide) {
@@ -1163,7 +1193,7 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         const BluesteinWs bw{static_cast<cf*>(workspace), M, n_heads};
         // transforms wider than one LDS chunk go to the multi-workgroup sequence, unless the cutoff has to be found
         // from the whole spectrum first
-        const bool wide = max_log >= kWideMinLog && g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && !cutoffs_only;
+        const bool wide = pl.any_wide && g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && !cutoffs_only;
         hipLaunchKernelGGL(smooth_bluestein_kernel, dim3(n_heads), dim3(kFftThreads), bluestein_smem(g, M), s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
                            cutoffs_only ? 1 : 0, wide ? 1 : 0);
