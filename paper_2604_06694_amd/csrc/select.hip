@@ -251,7 +251,13 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
     for (int bit = 31; bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
         int c = 0;
-        for (int j = tid; j < n_cand; j += kSelThreads) c += order_key(s[j]) >= trial ? 1 : 0;
+        for (int j0 = tid; j0 < n_cand; j0 += 16 * kSelThreads) {      // 16 loads in flight: clamped address, masked count
+            float f[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) f[u] = s[min(j0 + u * kSelThreads, n_cand - 1)];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) c += (j0 + u * kSelThreads < n_cand && order_key(f[u]) >= trial) ? 1 : 0;
+        }
         const int t = block_count(c, slots, parity);
         parity ^= 1;
         if (t >= want) T = trial; else c_up = t;
@@ -262,13 +268,15 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
     for (int base = 0; base < n_cand; base += 32 * kSelThreads) {
         const int j0 = base + tid * 32;
         uint32_t mg = 0, me = 0;
+        float f[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) f[u] = s[min(j0 + u, n_cand - 1)];
+#pragma unroll
         for (int u = 0; u < 32; ++u) {
-            const int j = j0 + u;
-            if (j < n_cand) {
-                const uint32_t key = order_key(s[j]);
-                mg |= (key > T ? 1u : 0u) << u;
-                me |= (key == T ? 1u : 0u) << u;
-            }
+            const uint32_t key = order_key(f[u]);
+            const bool live = j0 + u < n_cand;
+            mg |= (live && key > T ? 1u : 0u) << u;
+            me |= (live && key == T ? 1u : 0u) << u;
         }
         int gt_before, eq_before;
         block_exscan2(__builtin_popcount(mg), __builtin_popcount(me), slots + 2 * kSelWaves, gt_before, eq_before);
