@@ -236,11 +236,11 @@ int32_t audiokv_compact(const audiokv_params* params,
  * n_items * n_kv_heads heads, all L_i equal). weights_dev: fp32
  * [n_items * n_kv_heads], one per KV head. Intermediate scores live in the
  * workspace. Outputs as in the per-stage calls; the result equals the five
- * calls composed. The budget allocation does not depend on the scores, so for
- * pools of 32 heads or more it is forked onto a helper stream owned by the
- * library (created on first use, default priority), together with the tables
- * that smoothing needs for lengths that are not powers of two, and joined back
- * into `stream` with events after the scoring; everything is ordered after prior work on
+ * calls composed. The budget allocation does not depend on the scores, nor do
+ * the tables that smoothing needs for lengths that are not powers of two: for
+ * pools of 32 heads or more, or when such tables are needed, they are forked
+ * onto a helper stream owned by the library (created on first use, default
+ * priority) and joined back into `stream` with events after the scoring; everything is ordered after prior work on
  * `stream` and before later work on it. Calls on different streams may be in
  * flight together (separate workspaces and outputs), also from several host
  * threads: the helper stream and its two events are shared, so the part of a

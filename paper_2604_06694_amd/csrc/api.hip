@@ -462,9 +462,13 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     const int n_seg = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? 1 : n_items;
     const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
     const bool prof = g_prof.enabled && g_prof.created;
-    // a small pool is allocated faster than a fork and a join are issued (55 us of host time): keep it in line then
-    const bool side = !prof && hps >= 32;
-    const bool side_filters = side && alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0;
+    // Work that does not depend on the scores goes to the helper stream, beside the score sweeps: the allocation, and
+    // for lengths that are not powers of two the chirp tables and filter spectra of the smoothing (35 us of small
+    // kernels). A small pool alone is allocated faster than a fork and a join are issued (55 us of host time): then
+    // everything stays in line.
+    const bool chirp = alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0;
+    const bool side = !prof && (hps >= 32 || chirp);
+    const bool side_filters = side && chirp;
     std::unique_lock<std::mutex> helper_lock(g_helper.mu, std::defer_lock);
     if (side) helper_lock.lock();
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
