@@ -227,6 +227,8 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
     const int32_t* __restrict__ cu_b, const int32_t* __restrict__ cu_seq, int32_t* __restrict__ indices)
 {
     __shared__ int slots[4 * kSelWaves];
+    __shared__ uint32_t short_list[kCompact * kSelThreads];
+    __shared__ int list_n;
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
@@ -247,8 +249,10 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
     // the largest T with #(key >= T) >= want, bit by bit; c_up ends as #(key > T): the count of the last trial that
     // failed, which is T + 1 (all lower bits of T are ones from there down)
     uint32_t T = 0;
-    int c_up = 0, parity = 0;
-    for (int bit = 31; bit >= 0; --bit) {
+    int c_lo = n_cand, c_up = 0, parity = 0;
+    int bit = 31;
+    bool narrow = false;
+    for (; bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
         int c = 0;
         for (int j0 = tid; j0 < n_cand; j0 += 16 * kSelThreads) {      // 16 loads in flight: clamped address, masked count
@@ -260,7 +264,52 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(
         }
         const int t = block_count(c, slots, parity);
         parity ^= 1;
-        if (t >= want) T = trial; else c_up = t;
+        if (t >= want) { T = trial; c_lo = t; } else { c_up = t; }
+        // the keys that the remaining bits can still tell apart are those whose upper bits equal T's: once they fit
+        // the short list, one more streaming pass collects them and the rest of the search never touches memory
+        if (bit > 0 && c_lo - c_up <= kCompact * kSelThreads) { narrow = true; break; }
+    }
+    if (narrow) {
+        const uint32_t hi_part = T >> bit;
+        if (tid == 0) list_n = 0;
+        __syncthreads();
+        for (int j0 = tid; j0 < n_cand; j0 += 16 * kSelThreads) {
+            float f[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) f[u] = s[min(j0 + u * kSelThreads, n_cand - 1)];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const uint32_t key = order_key(f[u]);
+                const bool mine = j0 + u * kSelThreads < n_cand && (key >> bit) == hi_part;
+                // the order of the list does not matter (it is only counted): one LDS add per wave and step
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(mine);
+                int base = 0;
+                if (m) {
+                    if ((tid & 63) == 0) base = atomicAdd(&list_n, __builtin_popcountll(m));
+                    base = __shfl(base, 0, 64);
+                    const int pos = base + __builtin_popcountll(m & ((1ull << (tid & 63)) - 1ull));
+                    if (mine && pos < kCompact * kSelThreads) short_list[pos] = key;   // (the counts say it always fits)
+                }
+            }
+        }
+        __syncthreads();
+        const int n_und = c_lo - c_up;                   // == list_n
+        const int c_above = c_up;
+        uint32_t ckey[kCompact];
+#pragma unroll
+        for (int e = 0; e < kCompact; ++e) {
+            const int i = tid + e * kSelThreads;
+            ckey[e] = i < n_und ? short_list[i] : 0u;
+        }
+        for (--bit; bit >= 0; --bit) {
+            const uint32_t trial = T | (1u << bit);
+            int c = 0;
+#pragma unroll
+            for (int e = 0; e < kCompact; ++e) c += (tid + e * kSelThreads < n_und && ckey[e] >= trial) ? 1 : 0;
+            const int t = c_above + block_count(c, slots, parity);
+            parity ^= 1;
+            if (t >= want) T = trial; else c_up = t;
+        }
     }
     const int need_eq = want - c_up;
 
