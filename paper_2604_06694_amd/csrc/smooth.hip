@@ -20,6 +20,7 @@
 // M >= L + K - 1 rather than 2L - 1: half the size for most lengths at the usual cutoffs. Stages whose span
 // exceeds the LDS (M > 16384) run on global memory, the rest on 16384-point chunks inside LDS.
 #include <atomic>
+#include <type_traits>
 #include "common.h"
 
 namespace audiokv {
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
 
 constexpr int kChunkLog = 14;                     // 16384 complex = 128 KiB: the part of an FFT that fits in LDS
 constexpr int kWideMinLog = 12;                   // transforms of 4096 points and more are spread over four workgroups,
-constexpr int kWideMaxLog = 16;                   // up to the 65536 points that four LDS chunks hold
+constexpr int kWideMaxLog = 18;                   // in chunks of at most 16384 points: four up to 65536, then 8 or 16
 constexpr int kMaxBluesteinLog = 18;              // M <= 262144: any L <= 131072 at any cutoff
 __host__ __device__ inline bool wide_size(int logM) { return logM >= kWideMinLog && logM <= kWideMaxLog; }
 
@@ -825,7 +826,9 @@ __device__ __forceinline__ bool wide_head(const Geom& g, const int32_t* __restri
     w.logM = bluestein_log(w.L, w.K);
     if (!wide_size(w.logM)) return false;              // small or very large: the single-workgroup kernel owns it
     w.M = 1 << w.logM;
-    w.extra = 2;                                       // two top stages, four chunks of M / 4 <= 16384 points
+    // two top stages and four chunks of M / 4 points up to M = 65536; beyond, as many top stages as it takes for
+    // a chunk to fit the LDS (8 or 16 chunks of 16384 points)
+    w.extra = w.logM - kChunkLog > 2 ? w.logM - kChunkLog : 2;
     w.R = 1 << w.extra;
     w.q = w.M >> w.extra;
     w.owner = owner_item(cu_seq, item, w.L);
@@ -840,8 +843,42 @@ __device__ __forceinline__ cf root_m(int e, int M) {
     return {cs, -sn};
 }
 
+constexpr int kWideMaxR = 16;          // chunks per transform at most (M = 262144)
+
+// one radix-2 stage on the register values v[r] = x[i + r*q], partners HS chunks apart; `st` counts the stages from
+// the top (half-size M >> (st + 1)), so the twiddle is root_M^(offset in the half * 2^st)
+template <int HS>
+__device__ __forceinline__ void top_stage(cf* v, int R, int q, int i, int M, int st, bool inverse) {
+#pragma unroll
+    for (int r = 0; r < kWideMaxR; ++r) {
+        if ((r & HS) != 0 || r + HS >= kWideMaxR) continue;      // compile-time after unrolling
+        if (r + HS < R) {
+            const cf w = root_m(((r & (HS - 1)) * q + i) << st, M);
+            if (!inverse) { const cf d = csub(v[r], v[r + HS]); v[r] = cadd(v[r], v[r + HS]); v[r + HS] = cmul(d, w); }
+            else { const cf cw = cmul(v[r + HS], cconj(w)); v[r + HS] = csub(v[r], cw); v[r] = cadd(v[r], cw); }
+        }
+    }
+}
+
 // the top stage(s) on the R values v[r] = x[i + r*q] held in registers (see top_stages for the index algebra)
+template <int MAXR>
 __device__ __forceinline__ void top_butterfly(cf* v, int i, int M, int extra, bool inverse) {
+    if (MAXR > 4 && extra > 2) {
+        // 8 or 16 chunks: three or four plain radix-2 stages, largest half-size first forwards, last backwards
+        const int R = 1 << extra, q = M >> extra;
+        if (!inverse) {
+            if (extra == 4) top_stage<8>(v, R, q, i, M, 0, false);
+            top_stage<4>(v, R, q, i, M, extra - 3, false);
+            top_stage<2>(v, R, q, i, M, extra - 2, false);
+            top_stage<1>(v, R, q, i, M, extra - 1, false);
+        } else {
+            top_stage<1>(v, R, q, i, M, extra - 1, true);
+            top_stage<2>(v, R, q, i, M, extra - 2, true);
+            top_stage<4>(v, R, q, i, M, extra - 3, true);
+            if (extra == 4) top_stage<8>(v, R, q, i, M, 0, true);
+        }
+        return;
+    }
     if (extra == 1) {
         const cf w = root_m(i, M);
         if (!inverse) { const cf d = csub(v[0], v[1]); v[0] = cadd(v[0], v[1]); v[1] = cmul(d, w); }
@@ -884,19 +921,21 @@ __global__ __launch_bounds__(kWideThreads) void wide_prep_chirp_kernel(Geom g, c
     for (int n = blockIdx.x * kWideThreads + threadIdx.x; n < w.L; n += gridDim.x * kWideThreads) ch[n] = chirp(n, w.L);
 }
 
+template <int MAXR>
 __global__ __launch_bounds__(kWideThreads) void wide_prep_first_kernel(Geom g, const int32_t* __restrict__ cu_seq,
                                                                        double cutoff_frac, BluesteinWs ws)
 {
     WideHead w;
     const int item = blockIdx.y;
     if (!wide_owner(g, cu_seq, item, cutoff_frac, w)) return;
+    if (w.R > MAXR) return;                             // (the launcher picks the instantiation that holds every head)
     const int i = blockIdx.x * kWideThreads + threadIdx.x;
     if (i >= w.q) return;
     const cf* ch = ws.chirp_of(item);
     cf* B1 = ws.bhat_of(item, 0);
-    cf v[4];
+    cf v[MAXR];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < MAXR; ++r) {
         const int n = i + r * w.q;
         cf b = {0.f, 0.f};
         if (r < w.R) {
@@ -905,9 +944,9 @@ __global__ __launch_bounds__(kWideThreads) void wide_prep_first_kernel(Geom g, c
         }
         v[r] = b;
     }
-    top_butterfly(v, i, w.M, w.extra, false);
+    top_butterfly<MAXR>(v, i, w.M, w.extra, false);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < MAXR; ++r)
         if (r < w.R) B1[i + r * w.q] = v[r];
 }
 
@@ -927,6 +966,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_prep_second_kernel(Geom g, 
     }
 }
 
+template <int MAXR>
 __global__ __launch_bounds__(kWideThreads) void wide_first_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac,
     BluesteinWs ws)
@@ -934,27 +974,27 @@ __global__ __launch_bounds__(kWideThreads) void wide_first_kernel(
     WideHead w;
     const int head = blockIdx.y;
     if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    if (w.R > MAXR) return;                             // (the launcher picks the instantiation that holds every head)
     const int i = blockIdx.x * kWideThreads + threadIdx.x;
     if (i >= w.q) return;
     const float* src = in + w.off;
     const cf* ch = ws.chirp_of(w.owner);
     cf* A = ws.a_of(head);
-    cf v[4];
+    cf v[MAXR];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        if (r >= w.R) break;
+    for (int r = 0; r < MAXR; ++r) {          // (guards, not breaks: the loop must unroll for v to stay in registers)
         const int n = i + r * w.q;
         cf a = {0.f, 0.f};
-        if (n < w.L) {
+        if (r < w.R && n < w.L) {
             const cf c = ch[n];
             const float sv = pool_on_load ? pooled_at(src, w.L, n, g.pool_kernel, g.pool_mode) : src[n];
             a = {sv * c.re, sv * c.im};
         }
         v[r] = a;
     }
-    top_butterfly(v, i, w.M, w.extra, false);
+    top_butterfly<MAXR>(v, i, w.M, w.extra, false);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < MAXR; ++r)
         if (r < w.R) A[i + r * w.q] = v[r];
 }
 
@@ -998,12 +1038,14 @@ __global__ __launch_bounds__(kFftThreads) void wide_chunk_kernel(
     chunk_store(x, z, C);
 }
 
+template <int MAXR>
 __global__ __launch_bounds__(kWideThreads) void wide_middle_kernel(
     Geom g, const int32_t* __restrict__ cu_seq, double cutoff_frac, BluesteinWs ws, int32_t* __restrict__ kstar_out)
 {
     WideHead w;
     const int head = blockIdx.y;
     if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    if (w.R > MAXR) return;                             // (the launcher picks the instantiation that holds every head)
     const int i = blockIdx.x * kWideThreads + threadIdx.x;
     const int kstar = (int)floor(cutoff_frac * (double)(w.L >> 1));
     if (kstar_out && i == 0) kstar_out[head] = kstar;
@@ -1012,16 +1054,15 @@ __global__ __launch_bounds__(kWideThreads) void wide_middle_kernel(
     cf* A = ws.a_of(head);
     const float inv_m = 1.0f / (float)w.M;
     const int T = g.taper_bins;
-    cf v[4];
+    cf v[MAXR];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
-    top_butterfly(v, i, w.M, w.extra, true);            // v[r] is now the convolution at position k = i + r*q
+    for (int r = 0; r < MAXR; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
+    top_butterfly<MAXR>(v, i, w.M, w.extra, true);            // v[r] is now the convolution at position k = i + r*q
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        if (r >= w.R) break;
+    for (int r = 0; r < MAXR; ++r) {
         const int k = i + r * w.q;
         cf o = {0.f, 0.f};
-        if (k < w.K) {
+        if (r < w.R && k < w.K) {
             const float wgt = mask_weight(k, kstar, T) * ((k == 0 || 2 * k == w.L) ? 1.f : 2.f);
             if (wgt > 0.f) {
                 const cf c = ch[k];
@@ -1032,12 +1073,13 @@ __global__ __launch_bounds__(kWideThreads) void wide_middle_kernel(
         }
         v[r] = o;
     }
-    top_butterfly(v, i, w.M, w.extra, false);
+    top_butterfly<MAXR>(v, i, w.M, w.extra, false);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < MAXR; ++r)
         if (r < w.R) A[i + r * w.q] = v[r];
 }
 
+template <int MAXR>
 __global__ __launch_bounds__(kWideThreads) void wide_last_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac,
     float alpha, float* __restrict__ out, BluesteinWs ws)
@@ -1045,6 +1087,7 @@ __global__ __launch_bounds__(kWideThreads) void wide_last_kernel(
     WideHead w;
     const int head = blockIdx.y;
     if (!wide_head(g, cu_seq, head, cutoff_frac, w)) return;
+    if (w.R > MAXR) return;                             // (the launcher picks the instantiation that holds every head)
     const int i = blockIdx.x * kWideThreads + threadIdx.x;
     if (i >= w.q) return;
     const float* src = in + w.off;
@@ -1052,21 +1095,21 @@ __global__ __launch_bounds__(kWideThreads) void wide_last_kernel(
     const cf* ch = ws.chirp_of(w.owner);
     const cf* A = ws.a_of(head);
     const float scale = 1.0f / (float)w.M / (float)w.L;
-    cf v[4];
+    cf v[MAXR];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
-    top_butterfly(v, i, w.M, w.extra, true);
+    for (int r = 0; r < MAXR; ++r) v[r] = r < w.R ? A[i + r * w.q] : cf{0.f, 0.f};
+    top_butterfly<MAXR>(v, i, w.M, w.extra, true);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        if (r >= w.R) break;
+    for (int r = 0; r < MAXR; ++r) {
         const int n = i + r * w.q;
-        if (n >= w.L) continue;
-        const cf y = cmul(ch[n], v[r]);
-        const float st = y.re * scale;
-        if (alpha == 1.f) dst[n] = st;
-        else {
-            const float s0 = pool_on_load ? pooled_at(src, w.L, n, g.pool_kernel, g.pool_mode) : src[n];
-            dst[n] = (1.f - alpha) * s0 + alpha * st;
+        if (r < w.R && n < w.L) {
+            const cf y = cmul(ch[n], v[r]);
+            const float st = y.re * scale;
+            if (alpha == 1.f) dst[n] = st;
+            else {
+                const float s0 = pool_on_load ? pooled_at(src, w.L, n, g.pool_kernel, g.pool_mode) : src[n];
+                dst[n] = (1.f - alpha) * s0 + alpha * st;
+            }
         }
     }
 }
@@ -1150,11 +1193,14 @@ hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const
     hipLaunchKernelGGL(bluestein_prepare_kernel, dim3(g.n_items), dim3(kFftThreads), bluestein_smem(g, M), s, cu_seqlens,
                        bw, cutoff_frac, g.cutoff_mode, g.taper_bins, wide ? 1 : 0);
     if (wide) {
-        const int extra_stages = 2;
+        const int extra_stages = pl.max_log - kChunkLog > 2 ? pl.max_log - kChunkLog : 2;    // of the largest transform
         const unsigned q = (unsigned)(M >> extra_stages);
         const dim3 ew((q + kWideThreads - 1) / kWideThreads, (unsigned)g.n_items);
         hipLaunchKernelGGL(wide_prep_chirp_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
-        hipLaunchKernelGGL(wide_prep_first_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
+        if (extra_stages <= 2)
+            hipLaunchKernelGGL(wide_prep_first_kernel<4>, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
+        else
+            hipLaunchKernelGGL(wide_prep_first_kernel<kWideMaxR>, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
         hipLaunchKernelGGL(wide_chunk_kernel, dim3((unsigned)1 << extra_stages, (unsigned)(g.n_items * g.H_kv)),
                            dim3(kFftThreads), bluestein_smem(g, M), s, g, cu_seqlens, cutoff_frac, bw, -1);
         hipLaunchKernelGGL(wide_prep_second_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw);
@@ -1198,18 +1244,25 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, bw, kstar_out,
                            cutoffs_only ? 1 : 0, wide ? 1 : 0);
         if (wide) {
-            const int extra_stages = 2;
+            const int extra_stages = max_log - kChunkLog > 2 ? max_log - kChunkLog : 2;      // of the largest transform
             const unsigned q = (unsigned)(M >> extra_stages);
             const dim3 ew((q + kWideThreads - 1) / kWideThreads, (unsigned)n_heads);
             const dim3 cw((unsigned)1 << extra_stages, (unsigned)n_heads);
             const size_t csm = bluestein_smem(g, M);
-            hipLaunchKernelGGL(wide_first_kernel, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
-                               cutoff_frac, bw);
-            hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 0);
-            hipLaunchKernelGGL(wide_middle_kernel, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw, kstar_out);
-            hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 1);
-            hipLaunchKernelGGL(wide_last_kernel, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
-                               cutoff_frac, (float)alpha, out, bw);
+            // instantiated for at most 4 chunks per transform (the usual case: everything in registers is small) and for 16
+            auto sequence = [&](auto maxr) {
+                constexpr int MAXR = decltype(maxr)::value;
+                hipLaunchKernelGGL(wide_first_kernel<MAXR>, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0,
+                                   cu_seqlens, cutoff_frac, bw);
+                hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 0);
+                hipLaunchKernelGGL(wide_middle_kernel<MAXR>, ew, dim3(kWideThreads), 0, s, g, cu_seqlens, cutoff_frac, bw,
+                                   kstar_out);
+                hipLaunchKernelGGL(wide_chunk_kernel, cw, dim3(kFftThreads), csm, s, g, cu_seqlens, cutoff_frac, bw, 1);
+                hipLaunchKernelGGL(wide_last_kernel<MAXR>, ew, dim3(kWideThreads), 0, s, g, in, pool_on_load ? 1 : 0,
+                                   cu_seqlens, cutoff_frac, (float)alpha, out, bw);
+            };
+            if (extra_stages <= 2) sequence(std::integral_constant<int, 4>{});
+            else sequence(std::integral_constant<int, kWideMaxR>{});
         }
     }
     return hipGetLastError();
