@@ -91,6 +91,19 @@ def test_cap_and_waterfill():
     assert b[2] == 48 and b[3] == 32            # 80 split 3:2
 
 
+def test_every_head_gets_window_plus_uniform_floor_by_hand():
+    # Eq. 1: b = w + r + share. n_keep = 50, w = 10, beta = 0.25: r = floor(0.25 * (50 - 10)) = 10 (a share of the
+    # non-window mean; not of n_keep, which would give 12). The head with weight 0 gets exactly w + r = 20, the other
+    # one the remaining 2 * 50 - 20 = 80.
+    b, cu = O.allocate(np.array([1.0, 0.0]), 100, 0.5, window=10, floor_frac=0.25)
+    assert list(b) == [80, 20] and list(cu) == [0, 80, 100]
+    # beta = 1: nothing left to share, every head gets n_keep whatever the weights
+    b, _ = O.allocate(np.array([0.9, 0.1, 0.0]), 100, 0.5, window=10, floor_frac=1.0)
+    assert list(b) == [50, 50, 50]
+    # round-half-up of ratio * L: 0.5 * 5 = 2.5 -> 3, 0.25 * 10 = 2.5 -> 3, 0.4 * 2048 = 819.2 -> 819
+    assert O.n_keep_of(0.5, 5) == 3 and O.n_keep_of(0.25, 10) == 3 and O.n_keep_of(0.4, 2048) == 819
+
+
 def test_ratio_one_keeps_everything():
     b, _ = O.allocate(_dirichlet(np.random.default_rng(1), 5), 77, 1.0, window=8)
     assert np.all(b == 77)
