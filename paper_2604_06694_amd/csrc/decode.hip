@@ -141,6 +141,15 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
             }
         }
     }
+    // the first V rows of phase 3 are requested now: their latency passes under the softmax statistics
+    const int c8 = tid % VPR, kq = tid / VPR;
+    constexpr int UN = 8;                                       // rows in flight per thread
+    u32x4 vv[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+        const int rc = min(kq + u * KQ, rows - 1);
+        vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vrow0 + (size_t)rc * D) + c8);
+    }
     __syncthreads();
 
     // ---- phase 2: per query head, max and sum over the chunk; logits become weights ----
@@ -167,21 +176,20 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     __syncthreads();
 
     // ---- phase 3: weights times V ----
-    const int c8 = tid % VPR, kq = tid / VPR;
     float acc[GP][8];
 #pragma unroll
     for (int qh = 0; qh < GP; ++qh)
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[qh][i] = 0.f;
-    constexpr int UN = 8;                                       // rows in flight per thread
     for (int r = kq; r < rows16; r += KQ * UN) {
-        u32x4 vv[UN];
         int rr[UN];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             rr[u] = r + u * KQ;
-            const int rc = min(rr[u], rows - 1);                // clamped rows carry weight 0 (or are skipped below)
-            vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vrow0 + (size_t)rc * D) + c8);
+            if (r != kq) {                                      // (the first batch is already on its way)
+                const int rc = min(rr[u], rows - 1);            // clamped rows carry weight 0 (or are skipped below)
+                vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vrow0 + (size_t)rc * D) + c8);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
