@@ -243,7 +243,11 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         for (int r = tid; r < T::ROWS; r += 64 * WR)
             lds_rc[r] = row_base + r < rows_pad ? cst[(size_t)head * rows_pad + row_base + r] : INFINITY;
 
-    // sweep 1: running max (base-2 units: logit * c) and sum for row row0 + rb*32 + l32 over this lane's keys
+    // sweep 1: reference (base-2 units: logit * c) and sum of exp2(logit * c - reference) for row
+    // row0 + rb*32 + l32 over this lane's keys. The reference is a logit that the row has met, not its running
+    // maximum: softmax statistics are shift-invariant, and fp32 leaves more than a hundred binary orders between a
+    // term of 1 and overflow. It is raised only when a block's terms grow past 2^64 (see reduce_end), so the common
+    // path spends no vector work on maxima or on rescaling the sum. -inf: the lane has not seen a visible key yet.
     float run_m[NB], run_l[NB];
 #pragma unroll
     for (int rb = 0; rb < NB; ++rb) { run_m[rb] = -INFINITY; run_l[rb] = 0.f; }
@@ -268,35 +272,48 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     };
 
     // --- reduction of one block, cut into KK slices -------------------------------------------------------------
-    float red_c[NB];                                    // sweep 1: base-2 reference of the block in flight
-    float red_s[2];                                     // partial sums (two chains)
+    float red_c[NB];                                    // sweep 1: the reference in use (run_m, or 0 while that is -inf)
+    float red_s[2];                                     // partial sums of row tile 0 (two chains)
+    float red_t[NB];                                    // sweep 1: partial sums of row tiles 1.. (slot 0 unused)
     // sweep 2: a lane always meets the same 16 rows of a row tile (c_row(i, g2)), so their constants stay in registers
     float rcv[NB][16];
     // The scale is read through this copy. The empty asm statements in run_block take it as an in/out operand, which
     // ties every slice of vector work to its place between two MFMAs (see there).
     float c_pin = c;
+    // sweep 1, first block of a workgroup's plain tiles: take the reference from the logits themselves
+    auto reference_from = [&](f32x16 (&a)[NB]) {
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
+            float mx = a[rb][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
+            run_m[rb] = mx * c;                         // c > 0: the scaled maximum is the maximum of the scaled logits
+            red_c[rb] = run_m[rb];
+        }
+    };
     auto reduce_begin = [&](auto masked_tag, f32x16 (&a)[NB], int j0b) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         red_s[0] = red_s[1] = 0.f;
-        if (!SWEEP2) {
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                if (MASKED) {
+        for (int rb = 0; rb < NB; ++rb) red_t[rb] = 0.f;
+        if (!SWEEP2) {
+            if (MASKED) {
+                // tiles with invisible (row, key) pairs: plain running-maximum bookkeeping (a few tiles per head)
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb) {
                     const int lv = last_visible(g, L, R, rowg0 + rb * 32 + l32);
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
                         if (j0b + c_row(i, g2) > lv) a[rb][i] = -INFINITY;
-                }
-                float mx = a[rb][0];
+                    float mx = a[rb][0];
 #pragma unroll
-                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
-                // c > 0, so the scaled maximum is the maximum of the scaled logits. Outside the masked tiles every
-                // logit is finite, and a reference of -inf (nothing seen yet) cannot survive the max.
-                const float m_new = fmaxf(run_m[rb], mx * c);
-                const float ms = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
-                red_c[rb] = ms;
-                run_l[rb] *= fast_exp2(run_m[rb] - ms);
-                run_m[rb] = m_new;
+                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
+                    const float m_new = fmaxf(run_m[rb], mx * c);
+                    const float ms = (m_new == -INFINITY) ? 0.f : m_new;
+                    run_l[rb] *= fast_exp2(run_m[rb] - ms);     // exp2(-inf) = 0 with run_l = 0: stays 0
+                    run_m[rb] = m_new;
+                    red_c[rb] = ms;
+                }
             }
         } else if (MASKED) {
 #pragma unroll
@@ -314,11 +331,11 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                 red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c_pin, -rcv[rb][i]));
             } else {
                 if (rb == 0) red_s[i & 1] += fast_exp2(fmaf(a[rb][i], c_pin, -red_c[rb]));
-                else         run_l[rb] += fast_exp2(fmaf(a[rb][i], c_pin, -red_c[rb]));
+                else         red_t[rb] += fast_exp2(fmaf(a[rb][i], c_pin, -red_c[rb]));
             }
         }
     };
-    auto reduce_end = [&](int cbuf, int kb) {
+    auto reduce_end = [&](f32x16 (&a)[NB], int cbuf, int kb) {
         if (SWEEP2) {
             // rows held by the other half of the wave; the other waves' rows are added by the loader wave
             // v_permlane32_swap trades lanes 32..63 of its first operand with lanes 0..31 of its second: afterwards
@@ -333,7 +350,35 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 #endif
             if (g2 == 0) lds_cols[cbuf * (WR * T::TK) + wave * T::TK + kb * 32 + l32] = v;
         } else {
-            run_l[0] += red_s[0] + red_s[1];
+            red_t[0] = red_s[0] + red_s[1];
+            // Terms are exp2(logit - reference) with a reference that may lie below the block's maximum. A block sum
+            // that has left [0, 2^64) (inf included) means the reference is stale for that row: raise it to the
+            // block's maximum, rescale what was summed so far and sum the block again, now with terms <= 1. The
+            // logits are still in the accumulator registers. Rare (the first block of a row is its reference, and
+            // logits seldom climb 64 binary orders above it), so the test is one compare per row tile and block.
+            float worst = red_t[0];
+#pragma unroll
+            for (int rb = 1; rb < NB; ++rb) worst = fmaxf(worst, red_t[rb]);
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(worst < 0x1p64f)) != 0, 0)) {
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb) {
+                    if (!(red_t[rb] < 0x1p64f)) {
+                        float mx = a[rb][0];
+#pragma unroll
+                        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, a[rb][i]);
+                        const float m_new = fmaxf(run_m[rb], mx * c);    // finite: the row has a finite reference
+                        run_l[rb] *= fast_exp2(run_m[rb] - m_new);
+                        run_m[rb] = m_new;
+                        red_c[rb] = m_new;
+                        float sum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[rb][i], c, -m_new));
+                        red_t[rb] = sum;
+                    }
+                }
+            }
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb) run_l[rb] += red_t[rb];
         }
     };
 
@@ -374,8 +419,8 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 #if defined(__HIP_DEVICE_COMPILE__)
                 if (DO_MFMA && DO_RED) {
                     if constexpr (NB == 1)      asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]));
-                    else if constexpr (NB == 2) asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(run_l[1]));
-                    else                        asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(run_l[1]), "+v"(run_l[NB - 1]));
+                    else if constexpr (NB == 2) asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(red_t[1]));
+                    else                        asm volatile("" : "+v"(c_pin), "+v"(am[rb]), "+v"(red_s[0]), "+v"(red_s[1]), "+v"(red_t[1]), "+v"(red_t[NB - 1]));
                 }
 #endif
             }
@@ -405,6 +450,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     if (t < t_plain_end) {
         // ---- pipelined part: blocks (t, 0), (t, 1), (t + 1, 0), ... ; acc0 holds even blocks, acc1 odd ones
         run_block(Y{}, N{}, N{}, acc0, slot_of(t), 0, 0, 0, acc1);           // prologue: MFMAs of the first block
+        if (!SWEEP2) reference_from(acc0);
         // its last steps did not prefetch: start the stream for the second block
         if (T::KB >= 2) {
             static_assert(T::KB == 1 || T::KB % 2 == 0, "the accumulator sets alternate by block parity");
@@ -423,12 +469,13 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                     if ((kb & 1) == 0) {
                         reduce_begin(N{}, acc0, t * T::TK + kb * 32);
                         run_block(Y{}, Y{}, Y{}, acc1, slot_m, kb_m, slot_n, kb_n, acc0);
+                        reduce_end(acc0, cbuf, kb);
                     } else {
                         reduce_begin(N{}, acc1, t * T::TK + kb * 32);
                         if (!wrap1 || more) run_block(Y{}, Y{}, Y{}, acc0, slot_m, kb_m, slot_n, kb_n, acc1);
                         else                run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
+                        reduce_end(acc1, cbuf, kb);
                     }
-                    reduce_end(cbuf, kb);
                 }
                 __syncthreads();
             }
@@ -440,14 +487,14 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                 reduce_begin(N{}, acc0, t * T::TK);
                 if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc1, slot_of(t + 1), 0, 0, 0, acc0);
                 else                     run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
-                reduce_end((t - t_begin) % 3, 0);
+                reduce_end(acc0, (t - t_begin) % 3, 0);
                 ++t;
                 __syncthreads();
                 if (t >= t_plain_end) break;
                 reduce_begin(N{}, acc1, t * T::TK);
                 if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc0, slot_of(t + 1), 0, 0, 0, acc1);
                 else                     run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
-                reduce_end((t - t_begin) % 3, 0);
+                reduce_end(acc1, (t - t_begin) % 3, 0);
                 ++t;
                 __syncthreads();
             }
@@ -461,7 +508,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
             run_block(Y{}, N{}, N{}, acc0, slot_of(t), kb, 0, 0, acc1);
             reduce_begin(Y{}, acc0, t * T::TK + kb * 32);
             run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
-            reduce_end(cbuf, kb);
+            reduce_end(acc0, cbuf, kb);
         }
         __syncthreads();
     }

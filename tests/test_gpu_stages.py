@@ -290,6 +290,29 @@ def test_score_variants(A):
     _score_case(A, 8, 2, 16, 128, [500], k_scale=6.0, seed=6)      # peaky softmax: large logits
 
 
+@pytest.mark.parametrize("shape", ["ramp", "step", "descent"])
+def test_score_logits_far_from_first_block(A, shape):
+    """Logits that climb (or fall) by far more than 64 binary orders after the first keys of a row: the row sums
+    are kept relative to a reference taken from the first block a lane meets, and this is the case in which that
+    reference has to be raised (ramp: several times; step: a single jump that overflows exp2; descent: never)."""
+    rng = np.random.default_rng(11)
+    H_q, H_kv, W, d, L = 14, 2, 32, 128, 3000
+    t = {"ramp": np.linspace(-4.0, 4.0, L), "step": np.where(np.arange(L) < L // 2, -4.0, 4.0),
+         "descent": np.linspace(4.0, -4.0, L)}[shape]
+    kk = t[None, :, None] * np.ones((H_kv, 1, d)) + 0.25 * rng.standard_normal((H_kv, L, d))
+    qq = rng.uniform(0.5, 2.0, size=(H_q, W, 1)) * np.ones((1, 1, d)) + 0.25 * rng.standard_normal((H_q, W, d))
+    qq[1::3] *= -1.0                                   # some query heads see the ramp the other way round
+    item = {"q_win": f64_to_bf16_bits(qq), "k": f64_to_bf16_bits(kk), "seqlen": L}
+    p = A.Params(H_q, H_kv, d, W)
+    s = A.score(p, bf16_tensor(item["q_win"].reshape(-1)), bf16_tensor(item["k"].reshape(-1)), [L])
+    torch.cuda.synchronize()
+    s = s.cpu().numpy().reshape(H_kv, L)
+    assert np.isfinite(s).all()
+    ref = O.score(bf16_bits_to_f64(item["q_win"]), bf16_bits_to_f64(item["k"]))
+    for h in range(H_kv):
+        assert rel_err(s[h], ref[h]) <= SCORE_RTOL, (shape, h, rel_err(s[h], ref[h]))
+
+
 def test_score_config1_workload(A):
     cfg = get_config(1)
     it = gen_item(cfg, 0)
