@@ -265,6 +265,25 @@ int32_t audiokv_evict_lse(const audiokv_params* params,
                           int32_t* budgets_dev, int32_t* cu_budgets_dev,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* audiokv_evict for callers that cannot allocate device memory or pass a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation. Same arguments and same results as audiokv_evict,
+ * without `workspace`: the scratch is a static device array of AUDIOKV_NOALLOC_SCRATCH_BYTES inside the library
+ * (every GPU the library runs on holds its own copy until the process ends). A batch whose
+ * audiokv_workspace_bytes exceeds that size is rejected with AUDIOKV_E_WORKSPACE_TOO_SMALL and nothing is enqueued
+ * (one layer of 4 KV heads x 32768 tokens needs about 1.2 MB). The call creates no stream or event and calls no
+ * allocating routine; all kernels, the budget allocation included, go to `stream` in order. The array is shared by
+ * all calls on a GPU: calls whose kernels may overlap on one GPU (different streams or host threads) race on it and
+ * must be serialised by the caller. Nothing in it needs to start at zero: every kernel writes what it later reads. */
+#define AUDIOKV_NOALLOC_SCRATCH_BYTES (8u << 20)
+int32_t audiokv_evict_noalloc(const audiokv_params* params,
+                              const void* q_win, const void* k, const void* v,
+                              const float* weights_dev, int32_t alloc_scope,
+                              const int32_t* cu_seqlens_dev, const int32_t* seqlens_host, int32_t n_items,
+                              double ratio, double cutoff_frac, double alpha,
+                              void* k_out, void* v_out, int32_t* indices_dev,
+                              int32_t* budgets_dev, int32_t* cu_budgets_dev,
+                              void* stream);
+
 /* The step after the path: one decoding step on the compacted cache (paper
  * Sec. 1 and Sec. 4.6: generation proceeds on the retained tokens only).
  * q_dev: bf16 [n_items][n_q_heads][head_dim], one new query per head;

@@ -12,11 +12,11 @@ run before the library exists.
 import importlib
 
 _BINDING_NAMES = (
-    "AudioKVError", "Params", "allocate", "compact", "decode_attend", "decode_workspace_bytes", "evict", "lib_path", "n_keep", "profile_enable",
+    "AudioKVError", "Params", "allocate", "compact", "decode_attend", "decode_workspace_bytes", "evict", "evict_noalloc", "lib_path", "n_keep", "profile_enable",
     "profile_read", "score", "select", "smooth", "smooth_cutoffs", "total_kept", "version", "workspace_bytes",
     "POOL_AVG", "POOL_MAX", "LAYOUT_HEAD_MAJOR", "LAYOUT_TOKEN_MAJOR", "SCOPE_ITEM", "SCOPE_GLOBAL",
     "CUTOFF_FRACTION", "CUTOFF_ENERGY", "CUTOFF_ENERGY_NO_DC",
-    "PROFILE_STAGES",
+    "PROFILE_STAGES", "NOALLOC_SCRATCH_BYTES",
 )
 
 

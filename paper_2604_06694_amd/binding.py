@@ -98,6 +98,8 @@ def _load() -> C.CDLL:
                                   vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.audiokv_evict_lse.argtypes = [pp, vp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
                                   vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.audiokv_evict_noalloc.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, f64, f64, f64,
+                                          vp, vp, vp, vp, vp, vp]
     lib.audiokv_decode_workspace_bytes.argtypes = [pp, i32, i64, C.POINTER(C.c_size_t)]
     lib.audiokv_decode_attend.argtypes = [pp, vp, vp, vp, vp, i32, i64, vp, vp, C.c_size_t, vp]
     lib.audiokv_profile_enable.argtypes = [i32]
@@ -105,7 +107,7 @@ def _load() -> C.CDLL:
     lib.audiokv_profile_read.argtypes = [C.POINTER(C.c_float)]
     lib.audiokv_profile_read.restype = i32
     for name in ("total_kept", "workspace_bytes", "score", "allocate", "smooth", "smooth_cutoffs", "select", "compact", "evict",
-                 "decode_workspace_bytes", "decode_attend", "score_lse", "evict_lse"):
+                 "decode_workspace_bytes", "decode_attend", "score_lse", "evict_lse", "evict_noalloc"):
         getattr(lib, "audiokv_" + name).restype = i32
     return lib
 
@@ -331,6 +333,23 @@ def evict(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weig
                               _ptr(o["cu_budgets"]), _ptr(ws), ws.numel(), _stream()))
     o["total_rows"] = rows
     o["workspace"] = ws
+    return o
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def evict_noalloc(p: Params, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, weights: torch.Tensor,
+                  seqlens: Sequence[int], ratio: float, cutoff_frac: float, alpha: float, outputs: dict, *,
+                  alloc_scope: int = SCOPE_GLOBAL, cu_seqlens: torch.Tensor) -> dict:
+    """audiokv_evict_noalloc: the caller brings every buffer (`outputs` with k_out, v_out, indices, budgets,
+    cu_budgets; `cu_seqlens` on the device); neither this function nor the library allocates device memory."""
+    cp = p.c()
+    o = outputs
+    _check(_lib.audiokv_evict_noalloc(C.byref(cp), _ptr(q_win), _ptr(k), _ptr(v), _ptr(weights), int(alloc_scope),
+                                      _ptr(cu_seqlens), _host_lens(seqlens), len(seqlens), float(ratio),
+                                      float(cutoff_frac), float(alpha), _ptr(o["k_out"]), _ptr(o["v_out"]),
+                                      _ptr(o["indices"]), _ptr(o["budgets"]), _ptr(o["cu_budgets"]), _stream()))
     return o
 
 

@@ -423,7 +423,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
                     const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
                     const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac, double alpha,
                     void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev, int32_t* cu_budgets_dev,
-                    void* workspace, size_t workspace_bytes, void* stream)
+                    void* workspace, size_t workspace_bytes, void* stream, bool in_line = false)
 {
     AUDIOKV_TRY(check_params(params, 1));
     if (n_items == 0) return AUDIOKV_OK;
@@ -461,13 +461,14 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
 
     const int n_seg = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? 1 : n_items;
     const int hps = alloc_scope == AUDIOKV_SCOPE_GLOBAL ? n_heads : params->n_kv_heads;
-    const bool prof = g_prof.enabled && g_prof.created;
+    // in_line: everything on the caller's stream, no library-owned stream or event is touched (or created)
+    const bool prof = !in_line && g_prof.enabled && g_prof.created;
     // Work that does not depend on the scores goes to the helper stream, beside the score sweeps: the allocation, and
     // for lengths that are not powers of two the chirp tables and filter spectra of the smoothing (35 us of small
     // kernels). A small pool alone is allocated faster than a fork and a join are issued (55 us of host time): then
     // everything stays in line.
     const bool chirp = alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0;
-    const bool side = !prof && (hps >= 32 || chirp);
+    const bool side = !in_line && !prof && (hps >= 32 || chirp);
     const bool side_filters = side && chirp;
     std::unique_lock<std::mutex> helper_lock(g_helper.mu, std::defer_lock);
     if (side) helper_lock.lock();
@@ -538,6 +539,54 @@ int32_t audiokv_evict_lse(const audiokv_params* params, const void* q_win, const
     return evict_entry(params, q_win, k, v, lse_dev, weights_dev, alloc_scope, cu_seqlens_dev, seqlens_host, n_items,
                        ratio, cutoff_frac, alpha, k_out, v_out, indices_dev, budgets_dev, cu_budgets_dev, workspace,
                        workspace_bytes, stream);
+}
+
+// ---- audiokv_evict_noalloc: the workspace is a static device array -------------------------------------------------
+// One copy per GPU, at its own address; the host-side name `scratch` is only a handle for hipGetSymbolAddress.
+namespace {
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[AUDIOKV_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+struct ScratchAddr {
+    std::mutex mu;
+    void* ptr[kMaxDevices] = {};
+} g_scratch;
+
+// device address of `scratch` on the current device (looked up once per device, with that device current)
+int32_t scratch_of_current_device(void** out) {
+    int dev = -1;
+    AUDIOKV_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(AUDIOKV_E_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
+    if (!g_scratch.ptr[dev]) {
+        void* p = nullptr;
+        AUDIOKV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(AUDIOKV_E_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch.ptr[dev] = p;
+    }
+    *out = g_scratch.ptr[dev];
+    return AUDIOKV_OK;
+}
+}  // namespace
+
+int32_t audiokv_evict_noalloc(const audiokv_params* params, const void* q_win, const void* k, const void* v,
+                              const float* weights_dev, int32_t alloc_scope, const int32_t* cu_seqlens_dev,
+                              const int32_t* seqlens_host, int32_t n_items, double ratio, double cutoff_frac,
+                              double alpha, void* k_out, void* v_out, int32_t* indices_dev, int32_t* budgets_dev,
+                              int32_t* cu_budgets_dev, void* stream)
+{
+    AUDIOKV_TRY(check_params(params, 1));
+    if (n_items == 0) return AUDIOKV_OK;
+    Batch b;
+    AUDIOKV_TRY(check_batch(params, n_items, seqlens_host, &b));
+    const size_t need = plan_workspace(params, b, seqlens_host).total;
+    if (need > (size_t)AUDIOKV_NOALLOC_SCRATCH_BYTES)
+        return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "audiokv_evict_noalloc: this batch needs %zu bytes of scratch, the static "
+                    "array holds %zu (use audiokv_evict with a workspace)", need, (size_t)AUDIOKV_NOALLOC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    AUDIOKV_TRY(scratch_of_current_device(&ws));
+    return evict_entry(params, q_win, k, v, nullptr, weights_dev, alloc_scope, cu_seqlens_dev, seqlens_host, n_items,
+                       ratio, cutoff_frac, alpha, k_out, v_out, indices_dev, budgets_dev, cu_budgets_dev, ws,
+                       (size_t)AUDIOKV_NOALLOC_SCRATCH_BYTES, stream, /*in_line=*/true);
 }
 
 int32_t audiokv_decode_workspace_bytes(const audiokv_params* params, int32_t n_items, int64_t total_rows,

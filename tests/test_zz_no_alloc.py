@@ -1,0 +1,63 @@
+"""audiokv_evict_noalloc (scratch in a static device array) against audiokv_evict (caller's workspace), through the
+C ABI: two calls in a row on one GPU, the second with a smaller input, every output compared bit for bit; and the
+size limit. Collected last (file name), so that a failure here hides no other test."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import f64_to_bf16_bits
+
+from gpu_util import bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(A, rng, H_q, H_kv, d, W, lens, ratio, cutoff):
+    dev = torch.device("cuda:0")
+    q = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_q, W, d))).reshape(-1) for _ in lens]))
+    k = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_kv, L, d)) * 2.0).reshape(-1) for L in lens]))
+    v = bf16_tensor(np.concatenate([f64_to_bf16_bits(rng.standard_normal((H_kv, L, d))).reshape(-1) for L in lens]))
+    w = torch.from_numpy(rng.gamma(1.0, size=len(lens) * H_kv).astype(np.float32)).to(dev)
+    p = A.Params(H_q, H_kv, d, W)
+    ref = A.evict(p, q, k, v, w, lens, ratio, cutoff, 1.0, alloc_scope=A.SCOPE_ITEM)
+    torch.cuda.synchronize()
+    rows = ref["total_rows"]
+    n_heads = len(lens) * H_kv
+    out = {"k_out": torch.zeros((rows, d), dtype=torch.bfloat16, device=dev),
+           "v_out": torch.zeros((rows, d), dtype=torch.bfloat16, device=dev),
+           "indices": torch.full((rows,), -1, dtype=torch.int32, device=dev),
+           "budgets": torch.zeros(n_heads, dtype=torch.int32, device=dev),
+           "cu_budgets": torch.zeros(n_heads + 1, dtype=torch.int32, device=dev)}
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+    A.evict_noalloc(p, q, k, v, w, lens, ratio, cutoff, 1.0, out, alloc_scope=A.SCOPE_ITEM, cu_seqlens=cu)
+    torch.cuda.synchronize()
+    for name in ("budgets", "cu_budgets"):
+        assert torch.equal(out[name], ref[name]), name
+    assert torch.equal(out["indices"], ref["indices"][:rows]), "indices"
+    assert torch.equal(out["k_out"].view(torch.int16), ref["k_out"][:rows].view(torch.int16)), "k_out"
+    assert torch.equal(out["v_out"].view(torch.int16), ref["v_out"][:rows].view(torch.int16)), "v_out"
+
+
+def test_noalloc_matches_evict_on_two_calls_in_a_row():
+    import paper_2604_06694_amd as A
+    rng = np.random.default_rng(2024)
+    # the first call leaves the static array full of its scores; the second, smaller one must not see them
+    _case(A, rng, 28, 4, 128, 32, [8192, 3000], 0.4, 0.125)     # a power of two and a chirp-z length
+    _case(A, rng, 28, 4, 128, 32, [1500], 0.3, 0.25)
+    _case(A, rng, 8, 2, 256, 32, [2048], 0.4, 0.125)
+
+
+def test_noalloc_rejects_what_does_not_fit():
+    import paper_2604_06694_amd as A
+    from paper_2604_06694_amd import binding as B
+    p = A.Params(28, 4, 128, 32)
+    lens = [32768] * 28
+    assert A.workspace_bytes(p, lens) > A.NOALLOC_SCRATCH_BYTES
+    cp = p.c()
+    arr = (C.c_int32 * len(lens))(*lens)
+    one = C.c_void_p(256)          # never dereferenced: the size check comes first and nothing is enqueued
+    rc = B._lib.audiokv_evict_noalloc(C.byref(cp), one, one, one, one, 0, one, arr, len(lens), 0.4, 0.125, 1.0,
+                                      one, one, one, one, one, None)
+    assert rc == -3 and b"scratch" in B._lib.audiokv_last_error()
