@@ -21,6 +21,7 @@
 // exceeds the LDS (M > 16384) run on global memory, the rest on 16384-point chunks inside LDS.
 #include <atomic>
 #include <type_traits>
+#include <algorithm>
 #include "common.h"
 
 namespace audiokv {
@@ -226,6 +227,47 @@ __device__ __forceinline__ float mask_weight(int k, int kstar, int T) {
     return 0.5f * (1.f + cospif((float)(k - kstar) / (float)(T + 1)));
 }
 
+// Masks for which the filter needs no transform at all, and for which a transform would only add rounding noise to
+// what is exactly a plateau or exactly the input (the selection that follows breaks ties by index, so the noise
+// would decide instead): 2 = every bin is kept with weight 1 (Eq. 19 returns s itself), 1 = only the DC bin
+// survives (Eq. 19 returns the mean of s at every position), 0 = anything else.
+__host__ __device__ inline int degenerate_mask(int L, int kstar, int T) {
+    if (kstar >= (L >> 1)) return 2;
+    if (kstar + T == 0) return 1;
+    return 0;
+}
+
+// The result for a degenerate mask, by all kFftThreads threads of the workgroup; `part` holds kFftThreads doubles.
+// The mean is one value (float64 sum in a fixed order, rounded once), written to every position. In place is fine:
+// all reads of the mean case come before a barrier, and the copy case reads position n only to write position n.
+__device__ __forceinline__ void write_degenerate(int kind, const Geom& g, const float* src, float* dst, int L,
+                                                 int pool_on_load, float alpha, double* part) {
+    const int tid = threadIdx.x;
+    auto s_at = [&](int n) { return pool_on_load ? pooled_at(src, L, n, g.pool_kernel, g.pool_mode) : src[n]; };
+    if (kind == 2) {
+        for (int n = tid; n < L; n += kFftThreads) dst[n] = s_at(n);
+        return;
+    }
+    double mine = 0.0;
+    for (int n = tid; n < L; n += kFftThreads) mine += (double)s_at(n);
+    part[tid] = mine;
+    __syncthreads();
+    for (int off = kFftThreads >> 1; off > 0; off >>= 1) {
+        if (tid < off) part[tid] += part[tid + off];
+        __syncthreads();
+    }
+    const float mean = (float)(part[0] / (double)L);
+    if (alpha == 1.f && !pool_on_load) {
+        for (int n = tid; n < L; n += kFftThreads) dst[n] = mean;
+    } else {
+        // with pooling on load src and dst are different arrays; without it s_at(n) is src[n], read before written
+        for (int n = tid; n < L; n += kFftThreads) {
+            const float s0 = s_at(n);
+            dst[n] = alpha == 1.f ? mean : (1.f - alpha) * s0 + alpha * mean;
+        }
+    }
+}
+
 // LDS scratch of the energy search: kFftThreads partial sums and the result
 struct EnergyScratch {
     double part[kFftThreads];
@@ -294,6 +336,14 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     const int T = g.taper_bins;
     if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && cutoffs_only) {
         if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
+        return;
+    }
+
+    if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION &&
+        degenerate_mask(L, (int)floor(cutoff_frac * (double)(L >> 1)), T) == 2) {
+        // every bin kept: the filter is the identity (the DC-only mask needs nothing special here: with a single
+        // non-zero bin the inverse butterflies only add exact zeros, and every output is the same value)
+        write_degenerate(2, g, src, dst, L, pool_on_load, alpha, reinterpret_cast<double*>(smem));
         return;
     }
 
@@ -379,6 +429,11 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     }
     if (kstar_out && tid == 0) kstar_out[head] = kstar;
     if (cutoffs_only) return;
+    if (g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION && degenerate_mask(L, kstar, T) == 2) {
+        __syncthreads();                                        // everyone is done with the spectrum in LDS
+        write_degenerate(2, g, src, dst, L, pool_on_load, alpha, reinterpret_cast<double*>(smem));
+        return;
+    }
 
     // low-pass mask (Eq. 17-18) and back to the half-length form, pair (k, N-k) at a time. The transform sits in
     // bit-reversed order, so the loop runs over storage slots, not bins: slot p holds bin brev(p), consecutive
@@ -716,15 +771,24 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     const int tok0 = cu_seq[item];
     const int L = cu_seq[item + 1] - tok0;
     if (alpha == 0.f || pow2_length(L)) return;       // the LDS kernel owns this head
+    const int T = g.taper_bins;
+    // a fixed cutoff that leaves only the mean, or everything: no transform (this kernel owns such heads whatever
+    // the transform size would have been)
+    const int fixed_kind = g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION
+                               ? degenerate_mask(L, (int)floor(cutoff_frac * (double)(L >> 1)), T) : 0;
     // all but the small transforms are spread over several workgroups by the kernels below
-    if (skip_wide && wide_size(bluestein_log(L, wanted_bins(L, cutoff_frac, g.cutoff_mode, g.taper_bins)))) return;
+    if (skip_wide && fixed_kind == 0 &&
+        wide_size(bluestein_log(L, wanted_bins(L, cutoff_frac, g.cutoff_mode, g.taper_bins)))) return;
     const size_t off = (size_t)tok0 * g.H_kv + (size_t)h * L;
     const float* src = in + off;
     float* dst = out + off;
     const int tid = threadIdx.x;
-    const int T = g.taper_bins;
     if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && cutoffs_only) {
         if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
+        return;
+    }
+    if (fixed_kind != 0) {
+        write_degenerate(fixed_kind, g, src, dst, L, pool_on_load, alpha, reinterpret_cast<double*>(smem));
         return;
     }
     const int K = wanted_bins(L, cutoff_frac, g.cutoff_mode, T);
@@ -771,6 +835,13 @@ __global__ __launch_bounds__(kFftThreads) void smooth_bluestein_kernel(
     }
     if (kstar_out && tid == 0) kstar_out[head] = kstar;
     if (cutoffs_only) return;
+    if (g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION && degenerate_mask(L, kstar, T) != 0) {
+        // the energy rule left only the mean (usual when the DC bin is counted: it holds most of the energy of a
+        // non-negative sequence) or everything
+        __syncthreads();
+        write_degenerate(degenerate_mask(L, kstar, T), g, src, dst, L, pool_on_load, alpha, reinterpret_cast<double*>(smem));
+        return;
+    }
     for (int k = tid; k < M; k += kFftThreads) {
         cf v = {0.f, 0.f};
         if (k < K) {
@@ -822,6 +893,8 @@ __device__ __forceinline__ bool wide_head(const Geom& g, const int32_t* __restri
     const int tok0 = cu_seq[item];
     w.L = cu_seq[item + 1] - tok0;
     if (pow2_length(w.L)) return false;
+    // (the multi-workgroup sequence runs with a fixed cutoff only) masks that need no transform: single-workgroup kernel
+    if (degenerate_mask(w.L, (int)floor(cutoff_frac * (double)(w.L >> 1)), g.taper_bins) != 0) return false;
     w.K = wanted_bins(w.L, cutoff_frac, g.cutoff_mode, g.taper_bins);
     w.logM = bluestein_log(w.L, w.K);
     if (!wide_size(w.logM)) return false;              // small or very large: the single-workgroup kernel owns it
@@ -1175,7 +1248,7 @@ hipError_t smooth_kernel_attributes() {
 size_t bluestein_smem(const Geom& g, size_t M) {
     const size_t extra = g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION ? sizeof(EnergyScratch) + 2 * sizeof(cf) : 0;
     const size_t C = M < ((size_t)1 << kChunkLog) ? M : ((size_t)1 << kChunkLog);
-    return (padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra;
+    return std::max((padded_len(C) + kTwLo + (M >> 8) + 1) * sizeof(cf) + extra, (size_t)kFftThreads * sizeof(double));
 }
 }  // namespace
 
@@ -1225,7 +1298,9 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
     // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
     if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
         const int n_hi = (max_pow2 >> 8) + 1;
-        const size_t smem = (padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf) + extra;
+        // (at least the kFftThreads doubles that the no-transform paths reduce in)
+        const size_t smem = std::max((padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf) + extra,
+                                     (size_t)kFftThreads * sizeof(double));
         hipLaunchKernelGGL(smooth_pow2_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
                            pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, kstar_out, cutoffs_only ? 1 : 0);
     }

@@ -3,9 +3,9 @@ the synthetic workloads, through the C ABI.
 
 What is compared (per sampled head; budgets for every head):
   * budgets: bit-exact with the oracle's allocation;
-  * kept index sets: agreement >= 99.9 % on average, and every index on which
-    the two differ must sit at the budget threshold: its oracle score within
-    2e-3 * max|s_hat| of the oracle's b-th largest score;
+  * kept index sets: agreement >= 99.9 % on average (the achieved figure is printed), and every index on which
+    the two differ must tie with the budget threshold within the score tolerance: with floored magnitudes
+    m(x) = max(|x|, 1e-3 max|s_hat|), |s_hat[j] - threshold| <= 2e-3 (m(s_hat[j]) + m(threshold));
   * compacted K/V: byte-exact gather of the GPU's own indices (and therefore of
     the oracle's wherever the index sets agree);
   * the fused call equals the five per-stage calls composed, bit for bit.
@@ -96,27 +96,52 @@ def run_and_check(A, cfg, sample_heads, lens=None):
         assert np.array_equal(vo[cu_b[g]:cu_b[g + 1]], it["v"][h][mine])
 
     # sampled heads: against the oracle's scores and selection
-    agree = []
+    agree, worst_gap = [], 0.0
     for g in sample_heads:
         it, h = items[g // cfg.n_kv_heads], g % cfg.n_kv_heads
         L = it["seqlen"]
-        G = cfg.group
-        qf = bf16_bits_to_f64(it["q_win"][h * G:(h + 1) * G])
-        kf = bf16_bits_to_f64(it["k"][h:h + 1])
-        s = O.score(qf, kf, pool_kernel=cfg.pool_kernel)[0]
-        s_hat = O.smooth(s, cfg.cutoff, cfg.alpha)
+        s_hat = oracle_smoothed(cfg, it, g, h)
         ref = O.select(s_hat, int(ref_b[g]), cfg.window)
         mine = idx[cu_b[g]:cu_b[g + 1]]
         common = np.intersect1d(mine, ref)
         agree.append(len(common) / len(ref))
         diff = np.setxor1d(mine, ref)
         if len(diff):
+            # A token on which the two sides differ must tie with the budget threshold within what the score
+            # tolerance allows: both its score and the threshold score may be off by 2e-3 (floored relative).
             want = int(ref_b[g]) - cfg.window
             thr = np.sort(s_hat[:L - cfg.window])[::-1][want - 1]
-            tol = SCORE_RTOL * np.abs(s_hat).max()
-            assert np.all(np.abs(s_hat[diff] - thr) <= tol), (g, np.abs(s_hat[diff] - thr).max(), tol)
-    assert np.mean(agree) >= 0.999, agree
+            floor = 1e-3 * np.abs(s_hat).max()
+            tol = SCORE_RTOL * (np.maximum(np.abs(s_hat[diff]), floor) + max(abs(thr), floor))
+            gap = np.abs(s_hat[diff] - thr)
+            worst_gap = max(worst_gap, float((gap / tol).max()))
+            assert np.all(gap <= tol), (g, float((gap / tol).max()))
+    mean_agree = float(np.mean(agree)) if len(agree) else 1.0
+    assert mean_agree >= 0.999, f"mean index agreement {mean_agree:.6f} over heads {list(sample_heads)}: {agree}"
+    print(f"[{cfg.name} ratio={cfg.ratio} cutoff={cfg.cutoff}] heads {list(sample_heads)}: mean agreement "
+          f"{mean_agree:.6f}, min {min(agree) if agree else 1.0:.6f}, worst tie gap / tolerance {worst_gap:.3g}")
     return out, (items, lens, q, k, v, w, p, scope)
+
+
+_ORACLE_CACHE = {}
+
+
+def oracle_pooled(cfg, it, g, h):
+    """Oracle scores of head g (pooled, before smoothing); kept across the (ratio, cutoff) sweep of one workload."""
+    key = ("s", cfg.index, cfg.n_items, it["seqlen"], cfg.window, cfg.pool_kernel, g)
+    if key not in _ORACLE_CACHE:
+        G = cfg.group
+        qf = bf16_bits_to_f64(it["q_win"][h * G:(h + 1) * G])
+        kf = bf16_bits_to_f64(it["k"][h:h + 1])
+        _ORACLE_CACHE[key] = O.score(qf, kf, pool_kernel=cfg.pool_kernel)[0]
+    return _ORACLE_CACHE[key]
+
+
+def oracle_smoothed(cfg, it, g, h):
+    key = ("sh", cfg.index, cfg.n_items, it["seqlen"], cfg.window, cfg.pool_kernel, g, cfg.cutoff, cfg.alpha)
+    if key not in _ORACLE_CACHE:
+        _ORACLE_CACHE[key] = O.smooth(oracle_pooled(cfg, it, g, h), cfg.cutoff, cfg.alpha)
+    return _ORACLE_CACHE[key]
 
 
 def test_config1_full_and_fused_equals_composed(A):
@@ -145,11 +170,63 @@ def test_config2_qwen25_omni_stack(A):
     run_and_check(A, cfg, sample_heads=[0, 1, 2, 3, 57, 110, 111])
 
 
-@pytest.mark.parametrize("ratio,cutoff", [(0.4, 0.125), (0.2, 0.25), (0.2, 0.0625)])
+def _cfg3_heads(cfg):
+    """First and last layer, two in the middle, and the heads with the smallest and the largest budget."""
+    w = gen_weights(cfg)
+    heads = [0, 3, 58, 77, 108, 111, int(np.argmin(w)), int(np.argmax(w))]
+    extra = [g for g in (30, 90) if g not in heads]
+    return sorted(set(heads + extra))[:10]
+
+
+@pytest.mark.parametrize("ratio", [0.4, 0.2])
+@pytest.mark.parametrize("cutoff", [0.25, 0.125, 0.0625])
 def test_config3_long_audio_full_size(A, ratio, cutoff):
-    # the benchmark's launch configuration: all 28 layers of L = 32768 in one call
+    # the benchmark's launch configuration: all 28 layers of L = 32768 in one call; both retained ratios and the
+    # three cutoffs of the workload's sweep (the oracle's scores of the sampled heads are computed once)
     cfg = get_config(3, ratio=ratio, cutoff=cutoff)
-    run_and_check(A, cfg, sample_heads=[0, 3, 58, 111] if ratio == 0.4 else [5, 110])
+    heads = _cfg3_heads(cfg)
+    assert len(heads) >= 8
+    run_and_check(A, cfg, sample_heads=heads)
+
+
+def test_config3_score_and_smooth_values_full_size(A):
+    """Pooled and smoothed score VALUES at L = 32768, W = 64 (448 window rows, several key ranges per head, the
+    masked tail at that geometry), element by element against the oracle: in the benchmark's launch configuration
+    (all 28 layers in one call, sampled heads) and as a single-layer call (all four heads of one item)."""
+    cfg = get_config(3)
+    items, lens, q, k, v, w = make_batch(cfg)
+    p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window, pool_kernel=cfg.pool_kernel,
+                 floor_frac=cfg.floor_frac)
+    L = lens[0]
+
+    def check(s_gpu, sh_gpu, head_ids, cutoff, what):
+        for g in head_ids:
+            it, h = items[g // cfg.n_kv_heads], g % cfg.n_kv_heads
+            ref = oracle_pooled(cfg, it, g, h)
+            e = rel_err(s_gpu[g], ref)
+            assert e <= SCORE_RTOL, (what, "pooled", g, e)
+            assert np.abs(s_gpu[g] - ref).max() <= 1e-4 * np.abs(ref).max(), (what, "pooled abs", g)
+            ref_sh = O.smooth(ref, cutoff, cfg.alpha)
+            e = rel_err(sh_gpu[g], ref_sh)
+            assert e <= SCORE_RTOL, (what, "smoothed", g, e)
+            assert np.abs(sh_gpu[g] - ref_sh).max() <= 1e-4 * np.abs(ref_sh).max(), (what, "smoothed abs", g)
+
+    # all layers in one call
+    s_all = A.score(p, q, k, lens)
+    sh_all = A.smooth(p, s_all, lens, cfg.cutoff, cfg.alpha)
+    torch.cuda.synchronize()
+    s_np = s_all.cpu().numpy().reshape(cfg.n_items * cfg.n_kv_heads, L)
+    sh_np = sh_all.cpu().numpy().reshape(cfg.n_items * cfg.n_kv_heads, L)
+    check(s_np, sh_np, [0, 3, 58, 111], cfg.cutoff, "batched")
+    del s_all, sh_all
+    # one layer alone (another split of the keys into ranges): item 0, all four heads, the widest cutoff
+    per_q = cfg.n_q_heads * cfg.window * cfg.head_dim
+    per_kv = cfg.n_kv_heads * L * cfg.head_dim
+    s1 = A.score(p, q[:per_q], k[:per_kv], [L])
+    sh1 = A.smooth(p, s1, [L], 0.25, cfg.alpha)
+    torch.cuda.synchronize()
+    check(s1.cpu().numpy().reshape(cfg.n_kv_heads, L), sh1.cpu().numpy().reshape(cfg.n_kv_heads, L), [0, 1, 2, 3], 0.25,
+          "single layer")
 
 
 def test_config4_concentrated_weights(A):

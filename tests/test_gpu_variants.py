@@ -70,9 +70,11 @@ def run_variant(A, stack, *, weights=None, pool_kernel=7, pool_mode=0, cutoff=0.
         if len(diff):
             want = int(ref_b[g]) - W
             thr = np.sort(s_hat[:L - W])[::-1][want - 1]
-            tol = SCORE_RTOL * np.abs(s_hat).max()
-            assert np.all(np.abs(s_hat[diff] - thr) <= tol), (g, np.abs(s_hat[diff] - thr).max(), tol)
-    assert np.mean(agree) >= min_agree, np.mean(agree)
+            # a tie at the threshold within the score tolerance (floored relative, on both scores involved)
+            floor = 1e-3 * np.abs(s_hat).max()
+            tol = SCORE_RTOL * (np.maximum(np.abs(s_hat[diff]), floor) + max(abs(thr), floor))
+            assert np.all(np.abs(s_hat[diff] - thr) <= tol), (g, float((np.abs(s_hat[diff] - thr) / tol).max()))
+    assert np.mean(agree) >= min_agree, f"mean index agreement {np.mean(agree):.6f} (min {min(agree):.6f})"
     return budgets
 
 
