@@ -25,9 +25,6 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
-# plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one fp32 op per lane per clock
-# (packed-fp32 forms are compiled out), i.e. half of the 157.3 TFLOP/s FMA figure counted as ops
-ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def parse_args():

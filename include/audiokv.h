@@ -38,6 +38,8 @@
  *   K, V    bf16. Item i starts at element cu_seqlens[i] * n_kv_heads * head_dim.
  *           kv_layout 0: item block is [n_kv_heads][L_i][head_dim];
  *           kv_layout 1: item block is [L_i][n_kv_heads][head_dim].
+ *           Any other arrangement with contiguous rows: explicit strides in
+ *           audiokv_params (kv_stride_item / _head / _tok).
  *   q_win   bf16 [n_items][n_q_heads][window][head_dim]: the queries of the
  *           last `window` prompt positions (row w sits at position L_i - window + w).
  *           Query head q belongs to KV head q / (n_q_heads / n_kv_heads).
@@ -94,6 +96,19 @@ typedef struct audiokv_params {
     float    floor_frac;     /* beta in [0,1]: uniform floor r = floor(beta*(n_keep-W))*/
     int32_t  cutoff_mode;    /* AUDIOKV_CUTOFF_*: how the `cutoff_frac` argument of smooth / evict sets k* */
     int32_t  taper_bins;     /* T >= 0: bins of cosine roll-off after k* (0: hard mask) */
+    /* Explicit K/V strides, in elements; all three 0 (the default) selects the packed layout of `kv_layout`.
+     * Otherwise token j of KV head h of item i starts at element
+     *     i * kv_stride_item + h * kv_stride_head + j * kv_stride_tok
+     * of both `k` and `v` (kv_layout is then ignored; cu_seqlens still gives the lengths and the layout of the
+     * scores). A row is head_dim contiguous elements; every stride must be a multiple of 8 elements (rows are
+     * moved as 16-byte vectors), kv_stride_tok >= head_dim, and kv_stride_item > 0 when n_items > 1. Rows of
+     * different (item, head, token) must not overlap. This is how a padded prefill cache [B][H_kv][L_max][d]
+     * (kv_stride_item = H_kv*L_max*d, kv_stride_head = L_max*d, kv_stride_tok = d) or a slice of a larger
+     * buffer is passed without a copy. Used by score, compact, evict (and their variants); q_win, the outputs
+     * and the compacted cache read by decode_attend are always packed. */
+    int64_t  kv_stride_item;
+    int64_t  kv_stride_head;
+    int64_t  kv_stride_tok;
 } audiokv_params;
 
 /* Packed version: major * 10000 + minor * 100 + patch. */

@@ -10,9 +10,9 @@ What it computes (paper: AudioKV, Sec. 3):
   score     observation-window importance: the last W queries of every query
             head attend to all L keys of their KV head; row softmax; sum over
             window rows and over the query heads of the GQA group; local
-            pooling. (Sec. 3.3 calls this the per-head importance sequence
-            s in R^L, "averaged attention over a sliding decoding window";
-            Sec. 1/2 describe the local pooling of SnapKV-style scores.)
+            pooling. (Sec. 3.3: the per-head importance sequence s in R^L,
+            given there as attention averaged over a window of recent
+            queries; Sec. 1/2: local pooling of SnapKV-style scores.)
   allocate  head-wise budgets b = w + r + B_score * S / sum(S)  (Sec. 3.1,
             Eq. 1) with the floor of Sec. 3.2, Eq. 12, made to sum exactly to
             the total by a largest-remainder top-up.

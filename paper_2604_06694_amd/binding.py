@@ -42,6 +42,9 @@ class _CParams(C.Structure):
         ("floor_frac", C.c_float),
         ("cutoff_mode", C.c_int32),
         ("taper_bins", C.c_int32),
+        ("kv_stride_item", C.c_int64),
+        ("kv_stride_head", C.c_int64),
+        ("kv_stride_tok", C.c_int64),
     ]
 
 
@@ -59,15 +62,20 @@ class Params:
     floor_frac: float = 0.1
     cutoff_mode: int = CUTOFF_FRACTION
     taper_bins: int = 0
+    kv_stride_item: int = 0       # explicit K/V strides in elements; all 0: the packed layout of kv_layout
+    kv_stride_head: int = 0
+    kv_stride_tok: int = 0
 
     def key(self) -> tuple:
         return (self.n_q_heads, self.n_kv_heads, self.head_dim, self.window, self.pool_kernel, self.pool_mode,
-                self.causal, self.kv_layout, self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins)
+                self.causal, self.kv_layout, self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins,
+                self.kv_stride_item, self.kv_stride_head, self.kv_stride_tok)
 
     def c(self) -> _CParams:
         return _CParams(C.sizeof(_CParams), self.n_q_heads, self.n_kv_heads, self.head_dim, self.window,
                         self.pool_kernel, self.pool_mode, self.causal, self.kv_layout,
-                        self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins)
+                        self.softmax_scale, self.floor_frac, self.cutoff_mode, self.taper_bins,
+                        self.kv_stride_item, self.kv_stride_head, self.kv_stride_tok)
 
 
 def lib_path() -> str:

@@ -61,6 +61,17 @@ int32_t check_params(const audiokv_params* p, int window_min) {
         return fail(AUDIOKV_E_INVALID_ARG, "softmax_scale must be finite and >= 0 (0 selects 1/sqrt(d))");
     if (!(p->floor_frac >= 0.f && p->floor_frac <= 1.f))
         return fail(AUDIOKV_E_INVALID_ARG, "floor_frac must lie in [0, 1]");
+    if (p->kv_stride_tok != 0 || p->kv_stride_head != 0 || p->kv_stride_item != 0) {
+        // explicit strides: rows stay contiguous in head_dim and 16-byte aligned
+        if (p->kv_stride_tok < p->head_dim || p->kv_stride_head < 1 || p->kv_stride_item < 0)
+            return fail(AUDIOKV_E_INVALID_ARG, "kv strides (item %lld, head %lld, token %lld): with explicit strides the "
+                        "token stride must be >= head_dim, the head stride > 0 and the item stride >= 0",
+                        (long long)p->kv_stride_item, (long long)p->kv_stride_head, (long long)p->kv_stride_tok);
+        if (p->kv_stride_tok % 8 != 0 || p->kv_stride_head % 8 != 0 || p->kv_stride_item % 8 != 0)
+            return fail(AUDIOKV_E_INVALID_ARG, "kv strides (item %lld, head %lld, token %lld) must be multiples of 8 "
+                        "elements: K/V rows are moved as 16-byte vectors",
+                        (long long)p->kv_stride_item, (long long)p->kv_stride_head, (long long)p->kv_stride_tok);
+    }
     return AUDIOKV_OK;
 }
 
@@ -80,6 +91,8 @@ int32_t check_batch(const audiokv_params* p, int32_t n_items, const int32_t* seq
         b->total_tokens += L;
     }
     b->uniform = b->max_L == b->min_L;
+    if (p->kv_stride_tok != 0 && n_items > 1 && p->kv_stride_item == 0)
+        return fail(AUDIOKV_E_INVALID_ARG, "explicit kv strides with %d items need kv_stride_item > 0", n_items);
     if (b->total_tokens * p->n_kv_heads > (long long)INT32_MAX)
         return fail(AUDIOKV_E_UNSUPPORTED, "batch too large: %lld tokens x %d heads exceeds 2^31 scores",
                     b->total_tokens, p->n_kv_heads);
@@ -104,6 +117,9 @@ Geom make_geom(const audiokv_params* p, int n_items) {
     g.c_log2 = scale * 1.44269504088896340736f;
     g.cutoff_mode = p->cutoff_mode;
     g.taper_bins = p->taper_bins;
+    g.s_item = p->kv_stride_item;
+    g.s_head = p->kv_stride_head;
+    g.s_tok = p->kv_stride_tok;
     return g;
 }
 
@@ -344,12 +360,14 @@ int32_t smooth_entry(const audiokv_params* params, const float* scores_in, const
     AUDIOKV_TRY(check_smooth_args(params, cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
     void* fft_ws = nullptr;
-    if (alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0) {
-        const Workspace w = plan_workspace(&p2, b, seqlens_host);
-        if (!workspace || workspace_bytes < w.total)
+    const size_t fft_bytes = alpha != 0.0 ? smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) : 0;
+    if (fft_bytes > 0) {
+        // the stand-alone call uses the transform's scratch only, carved from the start of the workspace: whatever
+        // audiokv_workspace_bytes returns for the batch covers it (that size also holds the scores of the fused path)
+        if (!workspace || workspace_bytes < fft_bytes)
             return fail(AUDIOKV_E_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed (lengths that are not powers "
-                        "of two use a global-memory transform)", workspace ? workspace_bytes : (size_t)0, w.total);
-        fft_ws = static_cast<char*>(workspace) + w.fft_off;
+                        "of two use a global-memory transform)", workspace ? workspace_bytes : (size_t)0, fft_bytes);
+        fft_ws = workspace;
     }
     const Geom g = make_geom(params, n_items);
     AUDIOKV_HIP(launch_smooth(g, scores_in, false, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha,
@@ -388,7 +406,7 @@ int32_t audiokv_select(const audiokv_params* params, const float* scores, const 
     if (!scores || !budgets_dev || !cu_budgets_dev || !cu_seqlens_dev || !indices_dev)
         return fail(AUDIOKV_E_INVALID_ARG, "audiokv_select: NULL pointer argument");
     if (!select_supported(b.max_L))
-        return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d exceeds 32768", b.max_L);
+        return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d is not supported", b.max_L);
     const Geom g = make_geom(params, n_items);
     AUDIOKV_HIP(launch_select(g, scores, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev,
                               static_cast<hipStream_t>(stream)),
@@ -442,7 +460,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     AUDIOKV_TRY(check_smooth_args(params, cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
     AUDIOKV_TRY(check_score_shape(params));
-    if (!select_supported(b.max_L)) return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d exceeds 32768", b.max_L);
+    if (!select_supported(b.max_L)) return fail(AUDIOKV_E_UNSUPPORTED, "select: length %d is not supported", b.max_L);
     const int n_heads = n_items * params->n_kv_heads;
     if (alloc_scope == AUDIOKV_SCOPE_GLOBAL && n_heads > 1536)
         return fail(AUDIOKV_E_UNSUPPORTED, "global pool of %d heads > 1536", n_heads);

@@ -24,10 +24,19 @@ struct Geom {
     float c_log2;   // softmax scale * log2(e): logits are handled in base-2 units
     int cutoff_mode;   // AUDIOKV_CUTOFF_*
     int taper_bins;    // cosine roll-off bins after k*
+    // explicit K/V strides in elements (all zero: the packed layout named by `layout`)
+    int64_t s_item, s_head, s_tok;
 };
 
-// Where head (item, h), token j starts inside the packed K/V buffers (in elements).
-__device__ __forceinline__ int64_t kv_row_offset(const Geom& g, int64_t item_tok0, int L, int h, int j) {
+// Elements between consecutive tokens of one head.
+__device__ __forceinline__ int64_t kv_tok_stride(const Geom& g) {
+    if (g.s_tok) return g.s_tok;
+    return g.layout == AUDIOKV_LAYOUT_HEAD_MAJOR ? (int64_t)g.D : (int64_t)g.H_kv * g.D;
+}
+
+// Where head (item, h), token j starts inside the K/V buffers (in elements). item_tok0 = cu_seqlens[item].
+__device__ __forceinline__ int64_t kv_row_offset(const Geom& g, int item, int64_t item_tok0, int L, int h, int j) {
+    if (g.s_tok) return (int64_t)item * g.s_item + (int64_t)h * g.s_head + (int64_t)j * g.s_tok;
     const int64_t base = item_tok0 * g.H_kv * g.D;
     if (g.layout == AUDIOKV_LAYOUT_HEAD_MAJOR)
         return base + ((int64_t)h * L + j) * g.D;

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(
         const int L = cu_seq[item + 1] - tok0;
         // an index outside the item is a caller error; clamp so that it can never fault
         const int j = min(max(indices[p], 0), L - 1);
-        src[r] = kv_row_offset(g, tok0, L, h, j) / 8 + vec;   // in u32x4 units (8 bf16)
+        src[r] = kv_row_offset(g, item, tok0, L, h, j) / 8 + vec;   // in u32x4 units (8 bf16; strides are multiples of 8)
     }
     u32x4 kk[kRowsInFlight], vv[kRowsInFlight];
 #pragma unroll

@@ -182,19 +182,19 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         // The staged tile is carried in registers from one iteration to the next. Fold expressions give straight-line
         // code per piece, so the array is split into scalars before any loop transformation can get in the way.
         uint4 stage[T::CH];
-        // Rows of a head are a fixed number of elements apart in either layout, so a tile that lies wholly inside the
+        // Rows of a head are a fixed number of elements apart in every layout, so a tile that lies wholly inside the
         // sequence is addressed from one per-lane pointer and constants; only a tile that reaches past the end pays
         // for the clamp. (Recomputing every piece's 64-bit offset per tile cost the loader more vector instructions
         // than a compute wave spends on its MFMAs.)
-        const int64_t row_elems = (g.layout == AUDIOKV_LAYOUT_HEAD_MAJOR) ? (int64_t)D : (int64_t)g.H_kv * D;
-        const __bf16* lane_base = k + kv_row_offset(g, tok0, L, h, 0) + (int64_t)piece_row[0] * row_elems + part8;
+        const int64_t row_elems = kv_tok_stride(g);
+        const __bf16* lane_base = k + kv_row_offset(g, item, tok0, L, h, 0) + (int64_t)piece_row[0] * row_elems + part8;
         constexpr int ROWS_PER_PIECE = 64 / (D / 8);    // piece_row[it] = piece_row[0] + it * ROWS_PER_PIECE
         static_assert(64 % (D / 8) == 0, "a wave-wide load covers whole rows");
         auto fetch_one = [&](int it, int t_, bool inside) {
             if (inside)
                 return *reinterpret_cast<const uint4*>(lane_base + ((int64_t)t_ * T::TK + it * ROWS_PER_PIECE) * row_elems);
             const int j_ = min(t_ * T::TK + piece_row[it], L - 1);
-            return *reinterpret_cast<const uint4*>(k + kv_row_offset(g, tok0, L, h, j_) + part8);
+            return *reinterpret_cast<const uint4*>(k + kv_row_offset(g, item, tok0, L, h, j_) + part8);
         };
 #define AUDIOKV_FETCH(t_)    { const int tt_ = (t_); const bool in_ = (tt_ + 1) * T::TK <= L; [&]<size_t... I>(std::index_sequence<I...>) { ((stage[I] = fetch_one((int)I, tt_, in_)), ...); }(std::make_index_sequence<T::CH>{}); }
 #define AUDIOKV_DEPOSIT(s_)  { const int ss_ = (s_); [&]<size_t... I>(std::index_sequence<I...>) { ((*reinterpret_cast<uint4*>(lds + ss_ * T::LDS_K + piece_lds[I]) = stage[I]), ...); }(std::make_index_sequence<T::CH>{}); }

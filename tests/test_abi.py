@@ -64,11 +64,22 @@ def test_validation_errors_are_codes_not_crashes(A):
         (A.Params(28, 4, 128, 32, pool_kernel=4), -1),
         (A.Params(28, 4, 128, 32, floor_frac=1.5), -1),
         (A.Params(28, 4, 128, 32, kv_layout=7), -1),
+        # explicit K/V strides: rows are moved as 16-byte vectors and may not overlap within a head
+        (A.Params(28, 4, 128, 32, kv_stride_head=4096 * 128, kv_stride_tok=132), -1),     # token stride not a multiple of 8
+        (A.Params(28, 4, 128, 32, kv_stride_head=4096 * 128 + 4, kv_stride_tok=128), -1), # head stride not a multiple of 8
+        (A.Params(28, 4, 128, 32, kv_stride_head=4096 * 128, kv_stride_tok=64), -1),      # token stride below head_dim
+        (A.Params(28, 4, 128, 32, kv_stride_tok=128), -1),                                # head stride missing
+        (A.Params(28, 4, 128, 32, kv_stride_item=-8, kv_stride_head=4096 * 128, kv_stride_tok=128), -1),
     ]
     for p, code in cases:
         with pytest.raises(A.AudioKVError) as e:
             A.workspace_bytes(p, [2048])
         assert e.value.code == code
+    strided = A.Params(28, 4, 128, 32, kv_stride_head=4096 * 128, kv_stride_tok=128)
+    assert A.workspace_bytes(strided, [2048]) == A.workspace_bytes(good, [2048])      # one item: no item stride needed
+    with pytest.raises(A.AudioKVError) as e:
+        A.workspace_bytes(strided, [2048, 1000])  # several items need kv_stride_item
+    assert e.value.code == -1
     with pytest.raises(A.AudioKVError) as e:
         A.total_kept(good, [2048], 0.001)         # n_keep below the window
     assert e.value.code == -1
