@@ -65,16 +65,35 @@ struct Tile {
     static constexpr int TK = 32 * KB;                // keys per tile
     static constexpr int KK = D / 16;                 // MFMA k-steps per logit
     static constexpr int ROWS = NB * 32 * WR;         // padded window rows per head
-    static constexpr int ROW_BYTES = D * 2 + 16;      // LDS row pitch (16 B pad spreads the fragment reads over the banks)
+    // LDS rows are unpadded; the 16-byte chunk c of key row r sits at chunk slot c ^ (r & 7), which spreads the
+    // fragment reads (32 rows, same chunk) over the banks just as a padded pitch would, and lets a wave-wide
+    // load-to-LDS instruction, which can only fill 1 KiB of consecutive LDS bytes, deposit whole rows.
+    static constexpr int ROW_BYTES = D * 2;
+    static constexpr int CPR = D / 8;                 // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;              // rows per wave-wide load instruction
+    static_assert(64 % CPR == 0 && CPR >= 8, "a wave-wide load covers whole rows of at least 8 chunks");
     static constexpr int CHUNKS = TK * D / 8;         // 16-byte pieces per tile
-    static constexpr int CH = CHUNKS / 64;            // pieces per lane of the loader wave
+    static constexpr int CH = CHUNKS / 64;            // load instructions per tile
     static_assert(CHUNKS % 64 == 0, "a tile is a whole number of wave-wide 16-byte loads");
-    static constexpr int STAGES = 3;                  // LDS ring: loader runs two tiles ahead
+    // LDS ring: the loader wave requests tile t + AHEAD while tile t is consumed, straight from HBM into the ring
+    // (no staging registers), so AHEAD - 1 whole tiles are in flight across every barrier. Workgroups of one or two
+    // compute waves keep a shorter ring: there the number of resident workgroups matters more.
+    static constexpr int STAGES = (WR >= 4) ? 4 : 3;
+    static constexpr int AHEAD = STAGES - 1;
+    static_assert((AHEAD - 1) * CH <= 63, "the outstanding loads must fit the vmcnt field");
     static constexpr int LDS_K = TK * ROW_BYTES;      // one K buffer
     static constexpr int LDS_COLS = WR * TK * 4;      // one column-sum exchange buffer
     static constexpr int LDS_RC = ROWS * 4;           // sweep 2: per-row normalisation constants
     static constexpr int LDS_BYTES = STAGES * LDS_K + 3 * LDS_COLS + LDS_RC;
+    static constexpr int FLUSH_WAVE = (WR - 1 < 3) ? WR - 1 : 3;   // the compute wave that stores the column sums
 };
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and for nothing else
+// (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int vmcnt_only(int n) { return (n & 15) | (((n >> 4) & 3) << 14) | (7 << 4) | (15 << 8); }
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -144,6 +163,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     const int t_begin = split * tps;
     const int t_end = min(n_tiles, t_begin + tps);
 
+    const int n_loc = t_end - t_begin;                  // tiles of this workgroup
     if (t_begin >= t_end) {                           // uniform over the workgroup
         if (!SWEEP2) {
             float* my_stats = stats + ((size_t)head * nsplit + split) * rows_pad * 2;
@@ -154,9 +174,15 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 
     // sweep 2: add the WR waves' partial column sums of the tile starting at j0 (fixed order) and store them
     auto flush_cols = [&](int buf, int j0) {
+        // (the lane index passes through an empty asm so that the addresses are formed here, once per tile, instead
+        // of living in registers across the whole tile loop)
+        int lane_here = lane;
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("" : "+v"(lane_here));
+#endif
 #pragma unroll
         for (int cc = 0; cc < T::TK; cc += 64) {
-            const int col = cc + lane;
+            const int col = cc + lane_here;
             if (col < T::TK && j0 + col < L) {
                 float v = 0.f;
 #pragma unroll
@@ -166,59 +192,73 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         }
     };
 
+    // Workgroup barrier that orders LDS traffic only: the waves exchange nothing through global memory, and a wave's
+    // outstanding global loads or stores are no reason to hold the others up.
+    auto wg_barrier = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+    // sweep 2: one compute wave stores the column sums of tile t once the barrier that ended tile t has passed
+    auto flush_tile = [&](int t_) {
+        if (SWEEP2 && wave == T::FLUSH_WAVE) flush_cols((t_ - t_begin) % 3, t_ * T::TK);
+    };
+
     if (wave == WR) {
-        // ================= loader wave: HBM -> registers -> LDS ring, two tiles ahead =================
-        // Rows past the end are clamped to the last row, never zero-filled: every tile that reaches past
-        // L - W is a masked tile, and the masked path discards those logits.
-        // piece `it` of a tile is its 16-byte chunk it*64 + lane: a wave-wide load covers 1 KiB of consecutive rows
-        int piece_row[T::CH], piece_lds[T::CH];
-#pragma unroll
-        for (int it = 0; it < T::CH; ++it) {
-            const int cidx = it * 64 + lane;
-            piece_row[it] = cidx / (D / 8);
-            piece_lds[it] = piece_row[it] * T::ROW_BYTES + (cidx - piece_row[it] * (D / 8)) * 16;
-        }
-        const int part8 = (lane % (D / 8)) * 8;         // channel offset of this lane's chunk (same for all pieces)
-        // The staged tile is carried in registers from one iteration to the next. Fold expressions give straight-line
-        // code per piece, so the array is split into scalars before any loop transformation can get in the way.
-        uint4 stage[T::CH];
-        // Rows of a head are a fixed number of elements apart in every layout, so a tile that lies wholly inside the
-        // sequence is addressed from one per-lane pointer and constants; only a tile that reaches past the end pays
-        // for the clamp. (Recomputing every piece's 64-bit offset per tile cost the loader more vector instructions
-        // than a compute wave spends on its MFMAs.)
+        // ================= loader wave: HBM -> LDS ring, AHEAD tiles ahead =================
+        // Every instruction moves 64 x 16 bytes from per-lane global addresses to 1 KiB of consecutive LDS bytes
+        // (global_load_lds_dwordx4): lane l fills chunk slot l % CPR of row l / CPR of the instruction's RPI rows,
+        // so it fetches the chunk that belongs there under the swizzle. Rows past the end are clamped to the last
+        // row, never zero-filled: every tile that reaches past L - W is a masked tile, and the masked path
+        // discards those logits.
+        const int lrow = lane / T::CPR, pslot = lane % T::CPR;
         const int64_t row_elems = kv_tok_stride(g);
-        const __bf16* lane_base = k + kv_row_offset(g, item, tok0, L, h, 0) + (int64_t)piece_row[0] * row_elems + part8;
-        constexpr int ROWS_PER_PIECE = 64 / (D / 8);    // piece_row[it] = piece_row[0] + it * ROWS_PER_PIECE
-        static_assert(64 % (D / 8) == 0, "a wave-wide load covers whole rows");
-        auto fetch_one = [&](int it, int t_, bool inside) {
-            if (inside)
-                return *reinterpret_cast<const uint4*>(lane_base + ((int64_t)t_ * T::TK + it * ROWS_PER_PIECE) * row_elems);
-            const int j_ = min(t_ * T::TK + piece_row[it], L - 1);
-            return *reinterpret_cast<const uint4*>(k + kv_row_offset(g, item, tok0, L, h, j_) + part8);
+        const __bf16* head_base = k + kv_row_offset(g, item, tok0, L, h, 0);
+        // byte offset of this lane's chunk inside the RPI rows of instruction `it`, for it & 3 (the swizzle repeats
+        // every 8 rows): a 32-bit lane offset on top of a uniform 64-bit base keeps the address arithmetic scalar
+        unsigned lane_off[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            lane_off[v] = (unsigned)(((int64_t)lrow * row_elems + (pslot ^ ((v * T::RPI + lrow) & 7)) * 8) * 2);
+        auto issue_tile = [&](int lt) {                 // workgroup-local tile index; past the end: the last tile again,
+            const int t_ = t_begin + min(lt, n_loc - 1);   // into a slot whose tile has been consumed
+            unsigned char* dst = lds + (lt % T::STAGES) * T::LDS_K;
+            if ((t_ + 1) * T::TK <= L) {
+                const char* tile_base = reinterpret_cast<const char*>(head_base + (int64_t)t_ * T::TK * row_elems);
+#pragma unroll
+                for (int it = 0; it < T::CH; ++it)
+                    __builtin_amdgcn_global_load_lds(
+                        (global_void_ptr)(tile_base + (int64_t)it * T::RPI * row_elems * 2 + lane_off[it & 3]),
+                        (lds_void_ptr)(dst + it * 1024), 16, 0, 0);
+            } else {
+#pragma unroll
+                for (int it = 0; it < T::CH; ++it) {
+                    const int r_ = it * T::RPI + lrow;
+                    const int j_ = min(t_ * T::TK + r_, L - 1);
+                    __builtin_amdgcn_global_load_lds(
+                        (global_void_ptr)(k + kv_row_offset(g, item, tok0, L, h, j_) + (pslot ^ (r_ & 7)) * 8),
+                        (lds_void_ptr)(dst + it * 1024), 16, 0, 0);
+                }
+            }
         };
-#define AUDIOKV_FETCH(t_)    { const int tt_ = (t_); const bool in_ = (tt_ + 1) * T::TK <= L; [&]<size_t... I>(std::index_sequence<I...>) { ((stage[I] = fetch_one((int)I, tt_, in_)), ...); }(std::make_index_sequence<T::CH>{}); }
-#define AUDIOKV_DEPOSIT(s_)  { const int ss_ = (s_); [&]<size_t... I>(std::index_sequence<I...>) { ((*reinterpret_cast<uint4*>(lds + ss_ * T::LDS_K + piece_lds[I]) = stage[I]), ...); }(std::make_index_sequence<T::CH>{}); }
-        AUDIOKV_FETCH(t_begin)
-        AUDIOKV_DEPOSIT(0)
-        AUDIOKV_FETCH(min(t_begin + 1, t_end - 1))
-        AUDIOKV_DEPOSIT(1)
-        AUDIOKV_FETCH(min(t_begin + 2, t_end - 1))       // stays in registers until the first loop iteration
-        __syncthreads();
-        int slot_w = 2;                                 // ring slot of tile t + 2
-        for (int t = t_begin; t <= t_end; ++t) {        // one drain iteration more than there are tiles
-            // tile t + 2 was fetched during the previous iteration: its HBM latency hid behind a whole tile of
-            // compute. Its slot was last read in iteration t - 1, which ended with a barrier.
-            AUDIOKV_DEPOSIT(slot_w)
-            slot_w = (slot_w == T::STAGES - 1) ? 0 : slot_w + 1;
-            // unconditional (past the end it re-reads the last tile into a slot nobody reads again)
-            AUDIOKV_FETCH(min(t + 3, t_end - 1))
-            // column sums of tile t - 2 are complete and visible (written in iteration t - 2, barriers since)
-            if (SWEEP2 && t - 2 >= t_begin) flush_cols((t - 2 - t_begin) % 3, (t - 2) * T::TK);
-            __syncthreads();
+        // Loads complete in the order they were issued, so "at most (AHEAD - 1) tiles' worth outstanding" means
+        // that the oldest tile in flight has landed; the barrier then hands it to the compute waves. (These are the
+        // only vector-memory operations of this wave.)
+        auto tile_landed_then_barrier = [&]() {
+            __builtin_amdgcn_s_waitcnt(vmcnt_only((T::AHEAD - 1) * T::CH));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+        };
+#pragma unroll
+        for (int a = 0; a < T::AHEAD; ++a) issue_tile(a);
+        tile_landed_then_barrier();                     // tile 0 is in the ring
+#pragma unroll 1
+        for (int lt = 0; lt < n_loc; ++lt) {
+            // slot (lt + AHEAD) % STAGES held tile lt - 1, which every wave left at the barrier that ended it
+            issue_tile(lt + T::AHEAD);
+            tile_landed_then_barrier();                 // tile lt + 1 is in the ring; ends iteration lt
         }
-        if (SWEEP2) flush_cols((t_end - 1 - t_begin) % 3, (t_end - 1) * T::TK);
-#undef AUDIOKV_FETCH
-#undef AUDIOKV_DEPOSIT
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(0));      // nothing may still be writing LDS when the wave ends
         return;
     }
 
@@ -266,9 +306,14 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     static_assert(T::KK <= 16 ? (SLICE * T::KK == 16) : true, "reduction slices must cover the 16 elements");
     f32x16 acc0[NB], acc1[NB];
     bf16x8 kfr[RING];
+    // byte offset of chunk 2 kk + g2 of key row l32 (of any 32-key block: their first rows are multiples of 8) under
+    // the swizzle, for kk & 3; chunks 8 and up only add whole groups of 8 chunk slots
+    int frag_off[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) frag_off[v] = l32 * T::ROW_BYTES + (((2 * v) | g2) ^ (l32 & 7)) * 16;
     auto frag_load = [&](int slot, int kb, int kk, int ring) {   // keys kb*32 + l32, channels kk*16 + g2*8 .. +8
-        kfr[ring] = *reinterpret_cast<const bf16x8*>(lds + slot * T::LDS_K + (kb * 32 + l32) * T::ROW_BYTES +
-                                                     g2 * 16 + kk * 32);
+        kfr[ring] = *reinterpret_cast<const bf16x8*>(lds + slot * T::LDS_K + kb * 32 * T::ROW_BYTES + frag_off[kk & 3] +
+                                                     (kk >> 2) * 128);
     };
 
     // --- reduction of one block, cut into KK slices -------------------------------------------------------------
@@ -435,7 +480,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     const int t_plain_end = min(max(t_first_masked, t_begin), t_end);
     auto slot_of = [&](int t) { return (t - t_begin) % T::STAGES; };
 
-    __syncthreads();                                    // the first tiles are in the ring (and lds_rc is filled)
+    wg_barrier();                                       // the first tile is in the ring (and lds_rc is filled)
     if (SWEEP2) {
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb)
@@ -477,7 +522,8 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                         reduce_end(acc1, cbuf, kb);
                     }
                 }
-                __syncthreads();
+                wg_barrier();
+                flush_tile(t);
             }
         } else {
             // one block per tile: two tiles per trip so that the accumulator sets alternate statically. The MFMAs
@@ -488,15 +534,17 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                 if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc1, slot_of(t + 1), 0, 0, 0, acc0);
                 else                     run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
                 reduce_end(acc0, (t - t_begin) % 3, 0);
+                wg_barrier();
+                flush_tile(t);
                 ++t;
-                __syncthreads();
                 if (t >= t_plain_end) break;
                 reduce_begin(N{}, acc1, t * T::TK);
                 if (t + 1 < t_plain_end) run_block(Y{}, Y{}, N{}, acc0, slot_of(t + 1), 0, 0, 0, acc1);
                 else                     run_block(N{}, Y{}, N{}, acc0, 0, 0, 0, 0, acc1);
                 reduce_end(acc1, (t - t_begin) % 3, 0);
+                wg_barrier();
+                flush_tile(t);
                 ++t;
-                __syncthreads();
             }
         }
     }
@@ -510,9 +558,9 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
             run_block(N{}, Y{}, N{}, acc1, 0, 0, 0, 0, acc0);
             reduce_end(acc0, cbuf, kb);
         }
-        __syncthreads();
+        wg_barrier();
+        flush_tile(t);
     }
-    __syncthreads();                                    // the drain iteration of the loader wave
 
     if (!SWEEP2) {
         // a row's keys are spread over the two halves of the wave
