@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--no-per-layer", action="store_true", help="skip the one-launch-per-layer timing")
     ap.add_argument("--no-lse", action="store_true", help="skip the timing of the variant that is given the window's log-sum-exp")
     ap.add_argument("--no-decode", action="store_true", help="skip the timing of the decode-side consumer")
+    ap.add_argument("--no-data-probe", action="store_true", help="skip the timing of the score kernels on all-zero keys")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
@@ -108,29 +110,12 @@ def cpu_baseline(cfg, sample_items, w, ratio, cutoff, alpha, budget_s=12.0):
                       f"per-item budget pools); float64 numpy, BLAS threads as configured by the host"}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
-
+def load_workload(cfg, dev):
+    """Synthetic inputs of one workload, resident on the device; the first items are kept on the host for the oracle."""
     import numpy as np
     import torch
-    import paper_2604_06694_amd as A
-    from workloads import gen_item, gen_lengths, gen_weights, get_config
-
-    over = {}
-    if args.ratio is not None:
-        over["ratio"] = args.ratio
-    if args.cutoff is not None:
-        over["cutoff"] = args.cutoff
-    if args.seqlen is not None:
-        over["seqlen"] = args.seqlen
-    cfg = get_config(args.config, **over)
+    from workloads import gen_item, gen_lengths, gen_weights
     lens = [int(x) for x in gen_lengths(cfg)]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
     with cf.ThreadPoolExecutor(max_workers=8) as ex:
         items = list(ex.map(lambda i: gen_item(cfg, i, seqlen=lens[i]), range(cfg.n_items)))
 
@@ -140,10 +125,16 @@ def main():
 
     q, k, v = to_dev("q_win"), to_dev("k"), to_dev("v")
     w_host = gen_weights(cfg)
-    w = torch.from_numpy(w_host).to(dev)
-    sample_items = items[:8]
-    del items
+    return {"lens": lens, "q": q, "k": k, "v": v, "w_host": w_host, "w": torch.from_numpy(w_host).to(dev),
+            "sample_items": items[:8]}
 
+
+def time_config(A, cfg, data, steps, warmup, dev):
+    """Step time of the fused call on one workload, the duration of each of its kernels (HIP events recorded by the
+    library on the launch stream), the algorithmic rates and the dominant kernel against its bound."""
+    import numpy as np
+    import torch
+    lens, q, k, v, w = data["lens"], data["q"], data["k"], data["v"], data["w"]
     p = A.Params(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window, pool_kernel=cfg.pool_kernel,
                  floor_frac=cfg.floor_frac)
     scope = A.SCOPE_GLOBAL if cfg.alloc_scope == "global" else A.SCOPE_ITEM
@@ -155,26 +146,19 @@ def main():
         A.evict(p, q, k, v, w, lens, cfg.ratio, cfg.cutoff, cfg.alpha, alloc_scope=scope, cu_seqlens=cu,
                 workspace=ws, outputs=outs)
 
-    if args.pmc_calibration:
-        cal_src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).fill_(1)
-        cal_dst = torch.empty_like(cal_src)
-        cal_dst.copy_(cal_src)
-        torch.cuda.synchronize()
-        del cal_src, cal_dst
-
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
+    dt = (time.perf_counter() - t0) / steps
 
-    # per-kernel durations: the same steps again with HIP events recorded between the kernels on the launch stream
+    # the same steps again with HIP events recorded between the kernels on the launch stream
     A.profile_enable(True)
     acc = {n: 0.0 for n in A.PROFILE_STAGES}
-    n_prof = max(3, min(args.steps, 10))
+    n_prof = max(3, min(steps, 10))
     for _ in range(n_prof):
         # the events of the last of three back-to-back steps are read: a step that follows an idle GPU runs at a
         # higher clock than one inside a stream of steps, which is what the timed loop above and a profiler see
@@ -188,11 +172,8 @@ def main():
 
     tokens = sum(lens)
     kept = sum(A.n_keep(cfg.ratio, L) for L in lens)
-    evicted = tokens - kept
     ab = algorithmic_bytes(cfg, lens, cfg.ratio)
     score_flops = sum(2.0 * cfg.n_q_heads * cfg.window * L * cfg.head_dim for L in lens)
-    score_exps = sum(float(cfg.n_q_heads * cfg.window * L) for L in lens)
-
     dominant = max(stage_ms, key=stage_ms.get)
     dom_s = stage_ms[dominant] * 1e-3
     if dominant in ("score_sweep1", "score_sweep2"):
@@ -205,8 +186,67 @@ def main():
         roof = {"bound": "hbm", "achieved": ab[key] / dom_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    return {"dt": dt, "stage_ms": stage_ms, "tokens": tokens, "kept": kept, "ab": ab, "score_flops": score_flops,
+            "roof": roof, "p": p, "scope": scope, "cu": cu, "ws": ws, "outs": outs, "step": step}
+
+
+def other_config_line(A, index, steps, warmup, dev, **over):
+    """Compact record of another workload: the same measurement, fewer fields."""
+    import torch
+    from workloads import get_config
+    cfg = get_config(index, **over)
+    data = load_workload(cfg, dev)
+    m = time_config(A, cfg, data, steps, warmup, dev)
+    line = {"workload": cfg.name, "ratio": cfg.ratio, "ms_per_step": m["dt"] * 1e3,
+            "value": (m["tokens"] - m["kept"]) / m["dt"], "hbm_frac": m["ab"]["total"] / m["dt"] / 1e9 / HBM_PEAK_GBS,
+            "stage_ms": {n: round(x, 4) for n, x in m["stage_ms"].items()},
+            "dominant": {"kernel": m["roof"]["kernel"], "bound": m["roof"]["bound"], "frac": m["roof"]["frac"],
+                         "hbm_GBs_of_this_kernel": m["roof"].get("hbm_GBs_of_this_kernel")}}
+    del data, m
+    torch.cuda.empty_cache()
+    return line
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2604_06694_amd as A
+    from workloads import get_config
+
+    over = {}
+    if args.ratio is not None:
+        over["ratio"] = args.ratio
+    if args.cutoff is not None:
+        over["cutoff"] = args.cutoff
+    if args.seqlen is not None:
+        over["seqlen"] = args.seqlen
+    cfg = get_config(args.config, **over)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    data = load_workload(cfg, dev)
+    lens, q, k, v, w, w_host, sample_items = (data["lens"], data["q"], data["k"], data["v"], data["w"], data["w_host"],
+                                              data["sample_items"])
+
+    if args.pmc_calibration:
+        cal_src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).fill_(1)
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
+
+    m = time_config(A, cfg, data, args.steps, args.warmup, dev)
+    dt, stage_ms, p, scope, cu, ws, outs, step = (m["dt"], m["stage_ms"], m["p"], m["scope"], m["cu"], m["ws"], m["outs"],
+                                                  m["step"])
+    tokens, kept, ab, score_flops, roof = m["tokens"], m["kept"], m["ab"], m["score_flops"], m["roof"]
+    evicted = tokens - kept
+    score_exps = sum(float(cfg.n_q_heads * cfg.window * L) for L in lens)
     if args.ratio is None and args.cutoff is None and args.seqlen is None:
-        roof["traffic"] = measured_traffic(cfg.name).get(dominant)
+        roof["traffic"] = measured_traffic(cfg.name).get(roof["kernel"])
 
     res = {
         "metric": "prefill KV tokens evicted/sec per layer (1 GPU) + achieved HBM GB/s fraction",
@@ -352,8 +392,41 @@ def main():
         res["decode_consumer"] = {"ms_per_step": d_ms, "algorithmic_bytes": d_bytes, "GBs": d_bytes / d_ms / 1e6,
                                   "hbm_frac": d_bytes / d_ms / 1e6 / HBM_PEAK_GBS,
                                   "what": "single-query attention of all query heads over the compacted cache of all layers"}
+    if not args.no_data_probe:
+        # The score sweeps run the same instruction stream whatever the key values are; their duration is not the
+        # same: with all-zero keys (nothing toggles in the multipliers) they finish sooner. The ratio says how far the
+        # kernel time on real data is set by the chip's power management rather than by issue slots.
+        probe_out = torch.empty(sum(lens) * cfg.n_kv_heads, dtype=torch.float32, device=dev)
+
+        def timed_score(kk):
+            for _ in range(3):
+                A.score(p, q, kk, lens, cu_seqlens=cu, workspace=ws, out=probe_out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                A.score(p, q, kk, lens, cu_seqlens=cu, workspace=ws, out=probe_out)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / 10
+        real_ms = timed_score(k)
+        kz = torch.zeros_like(k)
+        zero_ms = timed_score(kz)
+        del kz, probe_out
+        res["score_time_vs_key_data"] = {"real_keys_ms": real_ms, "all_zero_keys_ms": zero_ms, "ratio": zero_ms / real_ms,
+                                         "what": "audiokv_score (both sweeps + pooling) on the workload's keys and on "
+                                                 "all-zero keys: identical instruction streams, different data"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, sample_items, w_host, cfg.ratio, cfg.cutoff, cfg.alpha)
+    if not args.no_other_configs and args.config == 3 and not over:
+        # every other workload, measured the same way in the same process (fewer steps); `value` stays on cfg 3
+        n_s, n_w = max(5, args.steps // 2), 3
+        res["other_configs"] = {
+            "cfg3_ratio0.2": other_config_line(A, 3, n_s, n_w, dev, ratio=0.2),
+            "cfg1": other_config_line(A, 1, n_s, n_w, dev),
+            "cfg2": other_config_line(A, 2, n_s, n_w, dev),
+            "cfg4": other_config_line(A, 4, n_s, n_w, dev),
+            "cfg5": other_config_line(A, 5, n_s, n_w, dev),
+        }
     print(json.dumps(res))
 
 
