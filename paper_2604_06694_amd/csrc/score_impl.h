@@ -65,9 +65,12 @@ struct Tile {
     static constexpr int TK = 32 * KB;                // keys per tile
     static constexpr int KK = D / 16;                 // MFMA k-steps per logit
     static constexpr int ROWS = NB * 32 * WR;         // padded window rows per head
-    // LDS rows are unpadded; the 16-byte chunk c of key row r sits at chunk slot c ^ (r & 7), which spreads the
-    // fragment reads (32 rows, same chunk) over the banks just as a padded pitch would, and lets a wave-wide
-    // load-to-LDS instruction, which can only fill 1 KiB of consecutive LDS bytes, deposit whole rows.
+    // LDS rows are unpadded; the 16-byte chunk c of key row r sits at chunk slot (c + r) mod 8 of its group of eight
+    // slots. That is bank for bank what a row pitch of d*2 + 16 bytes gives (slot s starts at bank 4 s mod 32), the
+    // layout under which the fragment reads (32 rows, same chunk) measure no bank conflict, while a wave-wide
+    // load-to-LDS instruction, which can only fill 1 KiB of consecutive LDS bytes, still deposits whole rows.
+    // (The bank-conflict counter still reads about 28 cycles per load-to-LDS instruction, whichever way the slots
+    // are permuted: that is how the incoming 1 KiB is written, not the fragment reads.)
     static constexpr int ROW_BYTES = D * 2;
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;              // rows per wave-wide load instruction
@@ -86,6 +89,9 @@ struct Tile {
     static constexpr int LDS_RC = ROWS * 4;           // sweep 2: per-row normalisation constants
     static constexpr int LDS_BYTES = STAGES * LDS_K + 3 * LDS_COLS + LDS_RC;
     static constexpr int FLUSH_WAVE = (WR - 1 < 3) ? WR - 1 : 3;   // the compute wave that stores the column sums
+    // chunk slot of chunk c of tile row r, and the chunk that slot s of row r holds
+    __host__ __device__ static constexpr int slot_of_chunk(int c, int r) { return (c & ~7) | ((c + r) & 7); }
+    __host__ __device__ static constexpr int chunk_in_slot(int s, int r) { return (s & ~7) | ((s - r) & 7); }
 };
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and for nothing else
@@ -208,18 +214,18 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
         // ================= loader wave: HBM -> LDS ring, AHEAD tiles ahead =================
         // Every instruction moves 64 x 16 bytes from per-lane global addresses to 1 KiB of consecutive LDS bytes
         // (global_load_lds_dwordx4): lane l fills chunk slot l % CPR of row l / CPR of the instruction's RPI rows,
-        // so it fetches the chunk that belongs there under the swizzle. Rows past the end are clamped to the last
+        // so it fetches the chunk that belongs in that slot. Rows past the end are clamped to the last
         // row, never zero-filled: every tile that reaches past L - W is a masked tile, and the masked path
         // discards those logits.
         const int lrow = lane / T::CPR, pslot = lane % T::CPR;
         const int64_t row_elems = kv_tok_stride(g);
         const __bf16* head_base = k + kv_row_offset(g, item, tok0, L, h, 0);
-        // byte offset of this lane's chunk inside the RPI rows of instruction `it`, for it & 3 (the swizzle repeats
-        // every 8 rows): a 32-bit lane offset on top of a uniform 64-bit base keeps the address arithmetic scalar
+        // byte offset of this lane's chunk inside the RPI rows of instruction `it`, for it & 3 (the slot rotation
+        // repeats every 8 rows): a 32-bit lane offset on top of a uniform 64-bit base keeps the address arithmetic scalar
         unsigned lane_off[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            lane_off[v] = (unsigned)(((int64_t)lrow * row_elems + (pslot ^ ((v * T::RPI + lrow) & 7)) * 8) * 2);
+            lane_off[v] = (unsigned)(((int64_t)lrow * row_elems + T::chunk_in_slot(pslot, v * T::RPI + lrow) * 8) * 2);
         auto issue_tile = [&](int lt) {                 // workgroup-local tile index; past the end: the last tile again,
             const int t_ = t_begin + min(lt, n_loc - 1);   // into a slot whose tile has been consumed
             unsigned char* dst = lds + (lt % T::STAGES) * T::LDS_K;
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
                     const int r_ = it * T::RPI + lrow;
                     const int j_ = min(t_ * T::TK + r_, L - 1);
                     __builtin_amdgcn_global_load_lds(
-                        (global_void_ptr)(k + kv_row_offset(g, item, tok0, L, h, j_) + (pslot ^ (r_ & 7)) * 8),
+                        (global_void_ptr)(k + kv_row_offset(g, item, tok0, L, h, j_) + T::chunk_in_slot(pslot, r_) * 8),
                         (lds_void_ptr)(dst + it * 1024), 16, 0, 0);
                 }
             }
@@ -306,11 +312,11 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     static_assert(T::KK <= 16 ? (SLICE * T::KK == 16) : true, "reduction slices must cover the 16 elements");
     f32x16 acc0[NB], acc1[NB];
     bf16x8 kfr[RING];
-    // byte offset of chunk 2 kk + g2 of key row l32 (of any 32-key block: their first rows are multiples of 8) under
-    // the swizzle, for kk & 3; chunks 8 and up only add whole groups of 8 chunk slots
+    // byte offset of chunk 2 kk + g2 of key row l32 (of any 32-key block: their first rows are multiples of 8) in its
+    // rotated slot, for kk & 3; chunks 8 and up only add whole groups of 8 chunk slots
     int frag_off[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) frag_off[v] = l32 * T::ROW_BYTES + (((2 * v) | g2) ^ (l32 & 7)) * 16;
+    for (int v = 0; v < 4; ++v) frag_off[v] = l32 * T::ROW_BYTES + T::slot_of_chunk((2 * v) | g2, l32) * 16;
     auto frag_load = [&](int slot, int kb, int kk, int ring) {   // keys kb*32 + l32, channels kk*16 + g2*8 .. +8
         kfr[ring] = *reinterpret_cast<const bf16x8*>(lds + slot * T::LDS_K + kb * 32 * T::ROW_BYTES + frag_off[kk & 3] +
                                                      (kk >> 2) * 128);
