@@ -360,7 +360,8 @@ int32_t smooth_entry(const audiokv_params* params, const float* scores_in, const
     AUDIOKV_TRY(check_smooth_args(params, cutoff_frac, alpha));
     AUDIOKV_TRY(check_smooth_lengths(b, seqlens_host, alpha));
     void* fft_ws = nullptr;
-    const size_t fft_bytes = alpha != 0.0 ? smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) : 0;
+    const size_t fft_bytes = alpha != 0.0 ? smooth_workspace_required(seqlens_host, n_items, params->n_kv_heads) : 0;
+    if (workspace && alpha != 0.0) fft_ws = workspace;      // optional room beyond the required part is put to use
     if (fft_bytes > 0) {
         // the stand-alone call uses the transform's scratch only, carved from the start of the workspace: whatever
         // audiokv_workspace_bytes returns for the batch covers it (that size also holds the scores of the fused path)
@@ -371,7 +372,8 @@ int32_t smooth_entry(const audiokv_params* params, const float* scores_in, const
     }
     const Geom g = make_geom(params, n_items);
     AUDIOKV_HIP(launch_smooth(g, scores_in, false, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac, alpha,
-                              scores_out, fft_ws, kstar_dev, cutoffs_only, static_cast<hipStream_t>(stream)),
+                              scores_out, fft_ws, fft_ws ? workspace_bytes : (size_t)0, kstar_dev, cutoffs_only,
+                              static_cast<hipStream_t>(stream)),
                 "smooth kernel");
     return AUDIOKV_OK;
 }
@@ -485,7 +487,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     // for lengths that are not powers of two the chirp tables and filter spectra of the smoothing (35 us of small
     // kernels). A small pool alone is allocated faster than a fork and a join are issued (55 us of host time): then
     // everything stays in line.
-    const bool chirp = alpha != 0.0 && smooth_workspace_bytes(seqlens_host, n_items, params->n_kv_heads) > 0;
+    const bool chirp = alpha != 0.0 && smooth_workspace_required(seqlens_host, n_items, params->n_kv_heads) > 0;
     const bool side = !in_line && !prof && (hps >= 32 || chirp);
     const bool side_filters = side && chirp;
     std::unique_lock<std::mutex> helper_lock(g_helper.mu, std::defer_lock);
@@ -521,7 +523,8 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
         helper_lock.unlock();
     }
     AUDIOKV_HIP(launch_smooth(g, raw, params->pool_kernel != 1, cu_seqlens_dev, seqlens_host, n_items, cutoff_frac,
-                              alpha, smoothed, ws + w.fft_off, nullptr, false, s, side_filters), "smooth kernel");
+                              alpha, smoothed, ws + w.fft_off, w.total - w.fft_off, nullptr, false, s, side_filters),
+                "smooth kernel");
     AUDIOKV_MARK(3);
     AUDIOKV_HIP(launch_select(g, smoothed, budgets_dev, cu_budgets_dev, cu_seqlens_dev, b.max_L, indices_dev, s),
                 "select kernel");

@@ -69,13 +69,17 @@ hipError_t launch_allocate(const Geom& g, const float* weights, int n_segments, 
 
 // pool_on_load: input holds un-pooled scores and the pooling of Geom is applied while loading.
 bool smooth_supported(int L);
-// Global-memory scratch of the arbitrary-length transform (0 when every length is a power of two).
+// Global-memory scratch of the smoothing: what the transforms of lengths that are not powers of two need
+// (_required: 0 when every length is a power of two), plus, for calls with few heads, room to spread a
+// power-of-two head over several workgroups (_bytes: the sum; what the workspace query reserves).
 size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv);
-// kstar_out (may be null): the cutoff bin of every head; cutoffs_only stops after writing it.
+size_t smooth_workspace_required(const int32_t* seqlens_host, int n_items, int H_kv);
+// kstar_out (may be null): the cutoff bin of every head; cutoffs_only stops after writing it. workspace_bytes: what
+// `workspace` holds (at least _required; with less than _bytes every power-of-two head runs in one workgroup).
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s,
-                         bool filters_ready = false);
+                         float* out, void* workspace, size_t workspace_bytes, int32_t* kstar_out, bool cutoffs_only,
+                         hipStream_t s, bool filters_ready = false);
 // Lengths that are not powers of two convolve with filters that depend on the lengths and the cutoff only:
 // launch_smooth_filters prepares them in the workspace (launch_smooth does it itself unless told they are ready).
 hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const int32_t* seqlens_host, int n_items,

@@ -584,9 +584,10 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
     }
 }
 
-// per row: max + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes.
-// One thread per row, 64 rows per workgroup. The per-range statistics are fetched eight at a time so that the
-// loads overlap instead of forming a chain of memory latencies as long as the number of ranges.
+// per row: reference + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes.
+// One thread per row, 64 rows per workgroup. The per-range statistics are fetched sixteen at a time, so that the
+// loads overlap instead of forming a chain of memory latencies as long as the number of ranges, and merged as they
+// come (one pass: a running reference and a sum rescaled when the reference rises).
 static __global__ __launch_bounds__(64) void score_merge_kernel(const float* __restrict__ stats, int nsplit,
                                                                 int rows_pad, int R, float* __restrict__ cst)
 {
@@ -597,21 +598,20 @@ static __global__ __launch_bounds__(64) void score_merge_kernel(const float* __r
     float out = INFINITY;
     if (r < R) {
         const float2* hs = reinterpret_cast<const float2*>(stats) + (size_t)head * nsplit * rows_pad + r;
-        float M = -INFINITY;
-        for (int s0 = 0; s0 < nsplit; s0 += 8) {
-            float2 v[8];
+        float M = -INFINITY, Z = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += 16) {
+            float2 v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
+            for (int u = 0; u < 16; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
+            float Mb = M;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) M = fmaxf(M, v[u].x);
-        }
-        float Z = 0.f;
-        for (int s0 = 0; s0 < nsplit; s0 += 8) {
-            float2 v[8];
+            for (int u = 0; u < 16; ++u)
+                if (s0 + u < nsplit && v[u].y > 0.f) Mb = fmaxf(Mb, v[u].x);
+            if (Mb == -INFINITY) continue;                  // nothing seen in these ranges either
+            Z *= fast_exp2(M - Mb);                         // exp2(-inf) = 0 while Z is still 0
+            M = Mb;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
                 if (s0 + u < nsplit && v[u].y > 0.f) Z += v[u].y * fast_exp2(v[u].x - M);
         }
         out = M + __log2f(Z);

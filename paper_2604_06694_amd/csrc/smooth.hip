@@ -81,6 +81,20 @@ __device__ __forceinline__ void pooled_pair_lds(const float* x, int L, int j0, i
     }
 }
 
+// Pooled values at positions j0 and j0 + 1 of x[0..L) (global memory or LDS): the common kernel sizes take all their
+// taps at once (independent loads), any other size goes tap by tap. Same bits either way.
+__device__ __forceinline__ void pooled_pair(const float* x, int L, int j0, int kernel, int mode, float& o0, float& o1) {
+    switch (kernel) {
+        case 3:  pooled_pair_lds<3>(x, L, j0, mode, o0, o1); break;
+        case 5:  pooled_pair_lds<5>(x, L, j0, mode, o0, o1); break;
+        case 7:  pooled_pair_lds<7>(x, L, j0, mode, o0, o1); break;
+        case 9:  pooled_pair_lds<9>(x, L, j0, mode, o0, o1); break;
+        default:
+            o0 = pooled_at(x, L, j0, kernel, mode);
+            o1 = pooled_at(x, L, j0 + 1, kernel, mode);
+    }
+}
+
 __global__ __launch_bounds__(256) void pool_kernel(Geom g, const float* __restrict__ raw,
                                                    const int32_t* __restrict__ cu_seq,
                                                    float* __restrict__ pooled)
@@ -139,7 +153,7 @@ __device__ __forceinline__ cf mul_root16(cf w, int k) {
 template <int R>
 __device__ __forceinline__ void dif_pass(cf* z, int n, int s, int tw_shift, const cf* lo, const cf* hi) {
     const int sb = s - R + 1;
-    for (int gi = threadIdx.x; gi < (n >> R); gi += kFftThreads) {
+    for (int gi = threadIdx.x; gi < (n >> R); gi += blockDim.x) {
         const int j0 = gi & ((1 << sb) - 1);
         const int base = ((gi >> sb) << (sb + R)) | j0;
         cf v[1 << R];
@@ -169,7 +183,7 @@ __device__ __forceinline__ void dif_pass(cf* z, int n, int s, int tw_shift, cons
 // R decimation-in-time stages (half-sizes 2^s0 up to 2^(s0+R-1)) with conjugate twiddles: the mirror image.
 template <int R>
 __device__ __forceinline__ void dit_pass(cf* z, int n, int s0, int tw_shift, const cf* lo, const cf* hi) {
-    for (int gi = threadIdx.x; gi < (n >> R); gi += kFftThreads) {
+    for (int gi = threadIdx.x; gi < (n >> R); gi += blockDim.x) {
         const int j0 = gi & ((1 << s0) - 1);
         const int base = ((gi >> s0) << (s0 + R)) | j0;
         cf v[1 << R];
@@ -311,10 +325,12 @@ __device__ __forceinline__ int energy_cutoff(EnergyFn&& energy, int n_bins, int 
     return sc->kstar;
 }
 
+__device__ __forceinline__ bool dec_owns(const Geom& g, int L, double cutoff_frac);   // heads of the several-workgroups path
+
 __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
     Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq,
     double cutoff_frac, float alpha,
-    float* __restrict__ out, int32_t* __restrict__ kstar_out, int cutoffs_only)
+    float* __restrict__ out, int32_t* __restrict__ kstar_out, int cutoffs_only, int skip_dec)
 {
     extern __shared__ float smem[];
     const int head = blockIdx.x;
@@ -333,6 +349,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
         return;
     }
     if (!pow2_length(L)) return;                      // the chirp-z kernel owns this head
+    if (skip_dec && dec_owns(g, L, cutoff_frac)) return;   // spread over several workgroups by the dec_* kernels
     const int T = g.taper_bins;
     if (g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && cutoffs_only) {
         if (tid == 0) kstar_out[head] = (int)floor(cutoff_frac * (double)(L >> 1));
@@ -373,15 +390,7 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
         for (int e = 0; e < kPer; ++e) {
             const int i = tid + e * kFftThreads;
             if (i < N) {
-                switch (g.pool_kernel) {
-                    case 3:  pooled_pair_lds<3>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
-                    case 5:  pooled_pair_lds<5>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
-                    case 7:  pooled_pair_lds<7>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
-                    case 9:  pooled_pair_lds<9>(rawf, L, 2 * i, g.pool_mode, keep[e].re, keep[e].im); break;
-                    default:
-                        keep[e].re = pooled_at(rawf, L, 2 * i, g.pool_kernel, g.pool_mode);
-                        keep[e].im = pooled_at(rawf, L, 2 * i + 1, g.pool_kernel, g.pool_mode);
-                }
+                pooled_pair(rawf, L, 2 * i, g.pool_kernel, g.pool_mode, keep[e].re, keep[e].im);
             }
         }
         __syncthreads();
@@ -495,6 +504,195 @@ __global__ __launch_bounds__(kFftThreads) void smooth_pow2_kernel(
         }
         dst[2 * i] = o0;
         dst[2 * i + 1] = o1;
+    }
+}
+
+// twiddle tables for the root exp(-2*pi*i/M): lo[t] = root^t (t < 128), hi[t] = root^(128 t), from float64 angles
+__device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
+    for (int t = threadIdx.x; t < kTwLo + n_hi; t += blockDim.x) {
+        const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
+        double sn, cs;
+        sincospi(2.0 * (double)e / (double)M, &sn, &cs);
+        const cf w = {(float)cs, (float)(-sn)};
+        if (t < kTwLo) lo[t] = w; else hi[t - kTwLo] = w;
+    }
+}
+
+// ------------------------ power-of-two lengths, few heads: one head on several workgroups ------------------------
+// A call with few heads (one layer of a prefill: four) leaves all but a handful of CUs idle while each head's
+// transform runs in one workgroup. For those calls a head of L = 2^p >= 1024 samples is cut into D = 16 interleaved
+// sub-sequences x_{16 m + r} of M = L / 16 samples, the first stage of a decimation-in-time FFT taken out of the
+// workgroup:
+//   dec_forward   per pair (r, r + 1): one complex M-point FFT in LDS gives the spectra G_r, G_{r+1} of the two
+//                 real sub-sequences (bins 0..M/2)                                          8 workgroups per head
+//   dec_combine   per bin j of the sub-spectra: F_{j + t M} = DFT16_r(w_L^{j r} G_r[j]) are the 16 bins of the
+//                 full spectrum in j's residue class; mask them (Eqs. 17-18); H_{r'}[j] =
+//                 w_L^{-j r'} IDFT16_t(F~_{j + t M})[r'] are the sub-spectra of the filtered sequence
+//   dec_inverse   per pair: one complex M-point inverse FFT returns s~_{16 m + r}, s~_{16 m + r + 1}; residual mix
+// Same arithmetic as the single-workgroup kernel up to the order of the butterflies (fp32, twiddles from float64 or
+// from exactly representable angles). Fixed-fraction cutoff only: an energy-adaptive cutoff needs the whole spectrum
+// in one place first.
+constexpr int kDecLog = 4, kDec = 1 << kDecLog;      // D
+constexpr int kDecThreads = 1024;    // the strided (and, inside evict, pooled) loads want many waves in flight
+constexpr int kDecMinL = 1024;
+constexpr int kDecMaxHeads = 64;                     // beyond this the heads fill the chip by themselves
+
+__host__ __device__ inline bool dec_length(int L) { return pow2_length(L) && L >= kDecMinL; }
+// complex values per head in the workspace: G and H, 16 sub-spectra of M/2 + 1 bins each
+__host__ __device__ inline size_t dec_head_elems(int L) { return 2 * (size_t)kDec * ((L >> (kDecLog + 1)) + 1); }
+
+struct DecWs {
+    cf* base;
+    size_t per_head;        // of the longest head of the batch
+    __device__ cf* g_of(int head, int r, int M) const { return base + (size_t)head * per_head + (size_t)r * ((M >> 1) + 1); }
+    __device__ cf* h_of(int head, int r, int M) const { return base + (size_t)head * per_head + (size_t)(kDec + r) * ((M >> 1) + 1); }
+};
+
+// which heads this path owns: identical test in all three kernels and in the single-workgroup kernel's skip
+__device__ __forceinline__ bool dec_owns(const Geom& g, int L, double cutoff_frac) {
+    return dec_length(L) && degenerate_mask(L, (int)floor(cutoff_frac * (double)(L >> 1)), g.taper_bins) != 2;
+}
+
+__global__ __launch_bounds__(kDecThreads) void dec_forward_kernel(
+    Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac, DecWs ws)
+{
+    extern __shared__ float smem[];
+    const int head = blockIdx.y, pr = blockIdx.x;
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    const int tok0 = cu_seq[item];
+    const int L = cu_seq[item + 1] - tok0;
+    if (!dec_owns(g, L, cutoff_frac)) return;
+    const int M = L >> kDecLog, logM = 31 - __clz(M);
+    const float* src = in + (size_t)tok0 * g.H_kv + (size_t)h * L;
+    cf* z = reinterpret_cast<cf*>(smem);
+    cf* lo = z + padded_len(M);
+    cf* hi = lo + kTwLo;
+    const int tid = threadIdx.x;
+    fill_tables(lo, hi, (M >> 8) + 1, M);
+    const int r0 = 2 * pr;
+    for (int m = tid; m < M; m += kDecThreads) {
+        const int n = (m << kDecLog) + r0;
+        cf v;
+        if (pool_on_load) pooled_pair(src, L, n, g.pool_kernel, g.pool_mode, v.re, v.im);
+        else { const float2 t = *reinterpret_cast<const float2*>(src + n); v.re = t.x; v.im = t.y; }
+        z[pad(m)] = v;
+    }
+    __syncthreads();
+    fft_lds(z, logM, logM - 1, false, lo, hi);        // bin k sits in slot brev(k)
+    const int shift = 32 - logM;
+    cf* G0 = ws.g_of(head, r0, M);
+    cf* G1 = ws.g_of(head, r0 + 1, M);
+    for (int j = tid; j <= (M >> 1); j += kDecThreads) {
+        const cf A = z[pad((int)(__brev((unsigned)j) >> shift))];
+        const cf B = cconj(z[pad((int)(__brev((unsigned)((M - j) & (M - 1))) >> shift))]);
+        G0[j] = {0.5f * (A.re + B.re), 0.5f * (A.im + B.im)};       // transform of the real parts
+        G1[j] = {0.5f * (A.im - B.im), -0.5f * (A.re - B.re)};      // -i (A - B) / 2: of the imaginary parts
+    }
+}
+
+// in-register 16-point DFT (forward: exp(-2 pi i / 16)); v[t] in, X[t] out
+__device__ __forceinline__ void dft16(cf (&v)[16]) {
+#pragma unroll
+    for (int half = 8; half >= 1; half >>= 1) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            if (q & half) continue;
+            const cf a = v[q], c = v[q | half];
+            v[q] = cadd(a, c);
+            v[q | half] = mul_root16(csub(a, c), (q & (half - 1)) * (8 / half));
+        }
+    }
+    // results are in bit-reversed order: swap in place
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int rq = ((q & 1) << 3) | ((q & 2) << 1) | ((q & 4) >> 1) | ((q & 8) >> 3);
+        if (rq > q) { const cf t = v[q]; v[q] = v[rq]; v[rq] = t; }
+    }
+}
+
+constexpr int kDecCombineThreads = 64;   // one bin per thread, many small workgroups
+
+__global__ __launch_bounds__(kDecCombineThreads) void dec_combine_kernel(
+    Geom g, const int32_t* __restrict__ cu_seq, double cutoff_frac, DecWs ws)
+{
+    const int head = blockIdx.y;
+    const int item = head / g.H_kv;
+    const int L = cu_seq[item + 1] - cu_seq[item];
+    if (!dec_owns(g, L, cutoff_frac)) return;
+    const int M = L >> kDecLog;
+    const int j = blockIdx.x * kDecCombineThreads + threadIdx.x;
+    if (j > (M >> 1)) return;
+    const int kstar = (int)floor(cutoff_frac * (double)(L >> 1));
+    const int T = g.taper_bins;
+    // twiddles w_L^{j r}: the angle 2 j r / L is exact in fp32 (j r < 2^15)
+    cf tw[kDec];
+#pragma unroll
+    for (int r = 0; r < kDec; ++r) {
+        float sn, cs;
+        sincospif(2.0f * (float)(j * r) / (float)L, &sn, &cs);
+        tw[r] = {cs, -sn};
+    }
+    cf v[kDec];
+#pragma unroll
+    for (int r = 0; r < kDec; ++r) v[r] = cmul(tw[r], ws.g_of(head, r, M)[j]);
+    dft16(v);                                          // v[t] = F_{j + t M}
+#pragma unroll
+    for (int t = 0; t < kDec; ++t) {
+        const int k = j + t * M;
+        const float wgt = mask_weight(k <= (L >> 1) ? k : L - k, kstar, T);
+        // conjugated for the inverse transform below: IDFT(x) = conj(DFT(conj(x)))
+        v[t] = {v[t].re * wgt, -v[t].im * wgt};
+    }
+    dft16(v);
+#pragma unroll
+    for (int r = 0; r < kDec; ++r) ws.h_of(head, r, M)[j] = cmul(cconj(tw[r]), cconj(v[r]));
+}
+
+__global__ __launch_bounds__(kDecThreads) void dec_inverse_kernel(
+    Geom g, const float* __restrict__ in, int pool_on_load, const int32_t* __restrict__ cu_seq, double cutoff_frac, float alpha,
+    float* __restrict__ out, DecWs ws)
+{
+    extern __shared__ float smem[];
+    const int head = blockIdx.y, pr = blockIdx.x;
+    const int item = head / g.H_kv, h = head - item * g.H_kv;
+    const int tok0 = cu_seq[item];
+    const int L = cu_seq[item + 1] - tok0;
+    if (!dec_owns(g, L, cutoff_frac)) return;
+    const int M = L >> kDecLog, logM = 31 - __clz(M);
+    const size_t off = (size_t)tok0 * g.H_kv + (size_t)h * L;
+    const float* src = in + off;
+    float* dst = out + off;
+    cf* z = reinterpret_cast<cf*>(smem);
+    cf* lo = z + padded_len(M);
+    cf* hi = lo + kTwLo;
+    const int tid = threadIdx.x;
+    fill_tables(lo, hi, (M >> 8) + 1, M);
+    const int r0 = 2 * pr, shift = 32 - logM;
+    const cf* H0 = ws.h_of(head, r0, M);
+    const cf* H1 = ws.h_of(head, r0 + 1, M);
+    // Z[j] = H0[j] + i H1[j] over all M bins; both sub-sequences are real, so bins above M/2 are conjugates
+    for (int j = tid; j < M; j += kDecThreads) {
+        const bool up = j > (M >> 1);
+        const int jj = up ? M - j : j;
+        cf a = H0[jj], b = H1[jj];
+        if (up) { a = cconj(a); b = cconj(b); }
+        z[pad((int)(__brev((unsigned)j) >> shift))] = {a.re - b.im, a.im + b.re};
+    }
+    __syncthreads();
+    fft_lds(z, logM, logM - 1, true, lo, hi);          // natural order out, unnormalised
+    const float inv = 1.0f / (float)L;
+    for (int m = tid; m < M; m += kDecThreads) {
+        const int n = (m << kDecLog) + r0;
+        const cf st = z[pad(m)];
+        float o0 = st.re * inv, o1 = st.im * inv;
+        if (alpha != 1.f) {
+            float a0, a1;
+            if (pool_on_load) pooled_pair(src, L, n, g.pool_kernel, g.pool_mode, a0, a1);
+            else { a0 = src[n]; a1 = src[n + 1]; }
+            o0 = (1.f - alpha) * a0 + alpha * o0;
+            o1 = (1.f - alpha) * a1 + alpha * o1;
+        }
+        *reinterpret_cast<float2*>(dst + n) = make_float2(o0, o1);
     }
 }
 
@@ -706,15 +904,6 @@ __device__ __forceinline__ int owner_item(const int32_t* __restrict__ cu_seq, in
     return item;
 }
 
-__device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
-    for (int t = threadIdx.x; t < kTwLo + n_hi; t += kFftThreads) {
-        const long long e = t < kTwLo ? t : (long long)(t - kTwLo) * kTwLo;
-        double sn, cs;
-        sincospi(2.0 * (double)e / (double)M, &sn, &cs);
-        const cf w = {(float)cs, (float)(-sn)};
-        if (t < kTwLo) lo[t] = w; else hi[t - kTwLo] = w;
-    }
-}
 
 // once per distinct length: the chirp table and the spectra of the two convolution filters.
 //   forward transform (L samples in, K bins out): conj(chirp(m)) for m in (-L, K), wrapped around M;
@@ -1200,15 +1389,38 @@ hipError_t launch_pool(const Geom& g, const float* raw, const int32_t* cu_seqlen
 
 bool smooth_supported(int L) { return pow2_length(L) || (L >= 1 && L <= 131072 && bluestein_log_max(L) <= kMaxBluesteinLog); }
 
-size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
-    // sized for the largest transform any cutoff can ask for (all bins wanted)
+namespace {
+// scratch of the chirp-z transforms (lengths that are not powers of two), sized for the largest transform any cutoff
+// can ask for (all bins wanted): per head the working array (M), per item the two filter spectra and the chirp table
+size_t bluestein_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
     int max_log = 0;
     for (int i = 0; i < n_items; ++i)
         if (!pow2_length(seqlens_host[i])) max_log = max(max_log, bluestein_log_max(seqlens_host[i]));
     if (max_log == 0) return 0;
     const size_t M = (size_t)1 << max_log;
-    // per head the working array (M), per item the two filter spectra and the chirp table (a slot of M each)
     return ((size_t)n_items * H_kv * M + (size_t)n_items * 3 * M) * sizeof(cf);
+}
+// sub-spectra of the several-workgroups path for power-of-two lengths (calls with few heads only)
+int dec_max_length(const int32_t* seqlens_host, int n_items, int H_kv) {
+    if ((long long)n_items * H_kv > kDecMaxHeads) return 0;
+    int mx = 0;
+    for (int i = 0; i < n_items; ++i)
+        if (dec_length(seqlens_host[i])) mx = max(mx, seqlens_host[i]);
+    return mx;
+}
+size_t dec_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
+    const int mx = dec_max_length(seqlens_host, n_items, H_kv);
+    return mx ? (size_t)n_items * H_kv * dec_head_elems(mx) * sizeof(cf) : 0;
+}
+}  // namespace
+
+// The two regions follow each other in the workspace (chirp-z first). Only the first is indispensable: without room
+// for the second, power-of-two heads simply stay on one workgroup each.
+size_t smooth_workspace_bytes(const int32_t* seqlens_host, int n_items, int H_kv) {
+    return bluestein_bytes(seqlens_host, n_items, H_kv) + dec_bytes(seqlens_host, n_items, H_kv);
+}
+size_t smooth_workspace_required(const int32_t* seqlens_host, int n_items, int H_kv) {
+    return bluestein_bytes(seqlens_host, n_items, H_kv);
 }
 
 namespace {
@@ -1283,8 +1495,8 @@ hipError_t launch_smooth_filters(const Geom& g, const int32_t* cu_seqlens, const
 
 hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, const int32_t* cu_seqlens,
                          const int32_t* seqlens_host, int n_items, double cutoff_frac, double alpha,
-                         float* out, void* workspace, int32_t* kstar_out, bool cutoffs_only, hipStream_t s,
-                         bool filters_ready)
+                         float* out, void* workspace, size_t workspace_bytes, int32_t* kstar_out, bool cutoffs_only,
+                         hipStream_t s, bool filters_ready)
 {
     if (cutoffs_only && !kstar_out) return hipErrorInvalidValue;
     const size_t extra = g.cutoff_mode != AUDIOKV_CUTOFF_FRACTION ? sizeof(EnergyScratch) + 2 * sizeof(cf) : 0;
@@ -1295,14 +1507,37 @@ hipError_t launch_smooth(const Geom& g, const float* in, bool pool_on_load, cons
         const hipError_t e = smooth_kernel_attributes();
         if (e != hipSuccess) return e;
     }
-    // every head is handled by exactly one of the two kernels (alpha = 0 copies: the first one)
-    if (max_pow2 > 0 || alpha == 0.0 || max_log == 0) {
+    // power-of-two heads of a call with few heads go over several workgroups each (fixed cutoff only)
+    const int dec_L = (alpha != 0.0 && !cutoffs_only && g.cutoff_mode == AUDIOKV_CUTOFF_FRACTION && workspace &&
+                       workspace_bytes >= smooth_workspace_bytes(seqlens_host, n_items, g.H_kv))
+                          ? dec_max_length(seqlens_host, n_items, g.H_kv) : 0;
+    const DecWs dw{reinterpret_cast<cf*>(static_cast<char*>(workspace) + bluestein_bytes(seqlens_host, n_items, g.H_kv)),
+                   dec_L ? dec_head_elems(dec_L) : 0};
+    // every head is handled by exactly one path (alpha = 0 copies: the single-workgroup kernel)
+    bool all_dec = dec_L > 0;
+    for (int i = 0; i < n_items && all_dec; ++i)
+        all_dec = dec_length(seqlens_host[i]) &&
+                  degenerate_mask(seqlens_host[i], (int)floor(cutoff_frac * (double)(seqlens_host[i] >> 1)), g.taper_bins) != 2;
+    if (!all_dec && (max_pow2 > 0 || alpha == 0.0 || max_log == 0)) {
         const int n_hi = (max_pow2 >> 8) + 1;
         // (at least the kFftThreads doubles that the no-transform paths reduce in)
         const size_t smem = std::max((padded_len((size_t)max_pow2 >> 1) + kTwLo + n_hi) * sizeof(cf) + extra,
                                      (size_t)kFftThreads * sizeof(double));
         hipLaunchKernelGGL(smooth_pow2_kernel, dim3(n_heads), dim3(kFftThreads), smem, s, g, in,
-                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, kstar_out, cutoffs_only ? 1 : 0);
+                           pool_on_load ? 1 : 0, cu_seqlens, cutoff_frac, (float)alpha, out, kstar_out, cutoffs_only ? 1 : 0,
+                           dec_L ? 1 : 0);
+    }
+    if (dec_L) {
+        const int M = dec_L >> kDecLog;
+        const size_t smem = (padded_len(M) + kTwLo + (M >> 8) + 1) * sizeof(cf);
+        const dim3 pairs(kDec / 2, (unsigned)n_heads);
+        hipLaunchKernelGGL(dec_forward_kernel, pairs, dim3(kDecThreads), smem, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
+                           cutoff_frac, dw);
+        hipLaunchKernelGGL(dec_combine_kernel,
+                           dim3((unsigned)(((M >> 1) + 1 + kDecCombineThreads - 1) / kDecCombineThreads), (unsigned)n_heads),
+                           dim3(kDecCombineThreads), 0, s, g, cu_seqlens, cutoff_frac, dw);
+        hipLaunchKernelGGL(dec_inverse_kernel, pairs, dim3(kDecThreads), smem, s, g, in, pool_on_load ? 1 : 0, cu_seqlens,
+                           cutoff_frac, (float)alpha, out, dw);
     }
     if (max_log > 0 && alpha != 0.0) {
         if (!workspace) return hipErrorInvalidValue;

@@ -231,3 +231,30 @@ def test_evict_energy_cutoff_on_ragged_lengths(A):
             ref = O.smooth(x, 0.0, 1.0, k_star=int(ks[i * H_kv + h]), taper_bins=3)
             assert rel_err(sh_host[off:off + L], ref) <= SCORE_RTOL
             off += L
+
+
+@pytest.mark.parametrize("L", [1024, 4096, 32768])
+@pytest.mark.parametrize("cutoff,alpha,T", [(0.125, 1.0, 0), (0.25, 0.5, 0), (0.0625, 1.0, 9), (0.9, 1.0, 0), (0.0, 1.0, 0)])
+def test_few_heads_path_matches_one_workgroup_per_head_and_the_oracle(A, L, cutoff, alpha, T):
+    """A call with few heads spreads every power-of-two head over several workgroups (interleaved sub-sequences);
+    a call with many heads keeps one workgroup per head. Same definition, different order of the butterflies: the
+    two agree to fp32 rounding, and both meet the oracle (the few-heads path also in place and with pooling fused
+    into its loads, as audiokv_evict uses it)."""
+    rng = np.random.default_rng(L + T)
+    H = 4
+    s = score_like(rng, H, L)
+    p = A.Params(H, H, 128, 1, taper_bins=T)
+    x = torch.from_numpy(s.reshape(-1)).cuda()
+    few = A.smooth(p, x, [L], cutoff, alpha).cpu().numpy().reshape(H, L)
+    n_rep = 20                                         # 80 heads: beyond the few-heads limit
+    many = A.smooth(p, x.repeat(n_rep), [L] * n_rep, cutoff, alpha).cpu().numpy().reshape(n_rep, H, L)
+    assert np.array_equal(many[0], many[-1])
+    for h in range(H):
+        ref = O.smooth(s[h].astype(np.float64), cutoff, alpha, taper_bins=T)
+        scale = np.abs(ref).max()
+        assert np.abs(few[h] - many[0][h]).max() <= 4e-6 * scale, (h, np.abs(few[h] - many[0][h]).max() / scale)
+        assert rel_err(few[h], ref) <= SCORE_RTOL and np.abs(few[h] - ref).max() <= 2e-5 * scale
+        assert rel_err(many[0][h], ref) <= SCORE_RTOL and np.abs(many[0][h] - ref).max() <= 2e-5 * scale
+    inplace = x.clone()
+    A.smooth(p, inplace, [L], cutoff, alpha, out=inplace)
+    assert np.array_equal(inplace.cpu().numpy().reshape(H, L), few)
