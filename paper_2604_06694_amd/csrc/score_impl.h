@@ -26,11 +26,14 @@
 // and a range of key tiles. The window queries are the stationary MFMA operand:
 // compute wave w keeps rows [w*NB*32, (w+1)*NB*32) as register fragments for
 // the whole kernel. K tiles (64 keys, or 32 at d = 256) are read from HBM once
-// per sweep by the loader wave (16-byte coalesced loads, two tiles ahead of the
-// compute waves, through a ring of three LDS buffers, one barrier per tile), so
-// the HBM latency is paid by a wave that has nothing else to do and the compute
-// waves hold no staging registers. Every compute wave pulls all 32-key x
-// 16-channel fragments of the tile. Sweep 1 computes
+// per sweep by the loader wave (16-byte load-to-LDS instructions that go from
+// HBM straight into a ring of three or four LDS buffers, two or three tiles
+// ahead of the compute waves, one barrier per tile), so the HBM latency is paid
+// by a wave that has nothing else to do and no wave holds staging registers.
+// Every compute wave pulls all 32-key x 16-channel fragments of the tile.
+// Sweep 1 keeps no running maximum: its exponentials are taken against a fixed
+// reference (the maximum of the wave's first block) and only a block whose sum
+// leaves the safe range is redone against a new reference. Sweep 1 computes
 // C = K Q^T (a lane owns one query row, so max/sum stay in the lane); sweep 2
 // computes C = Q K^T (a lane owns one key, so the column sum stays in the
 // lane). Both orientations use the same register fragments: only the operand
