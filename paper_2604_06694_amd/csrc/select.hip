@@ -5,13 +5,14 @@
 // registers (token t + 1024 e in register e of thread t: coalesced loads).
 // The value of the k-th largest key is found bit by bit (32 counting passes,
 // no atomics); once the keys that the remaining bits can still separate are
-// few, they are moved to a short list and only they are counted. Tokens above
-// the threshold are kept, tokens equal to it are kept in index order until the
-// budget is full: per-token bitmaps built from lane masks give every thread 32
-// consecutive tokens back, and kept indices are written in ascending order
-// through a block-wide exclusive scan (gathered in LDS, stored coalesced).
-// Integer-only: bit-exact.
-#include <atomic>
+// few, they are moved to a short list and only they are counted; once at most
+// 64 are left, one wave ranks them against each other and reads the threshold
+// off directly. Tokens above the threshold are kept, tokens equal to it are
+// kept in index order until the budget is full: for a fixed register the lanes
+// of a wave hold 64 consecutive tokens, so lane masks give every (register,
+// wave) chunk its counts, one block-wide exclusive scan over the chunks gives
+// their output offsets, and every kept token computes its own ascending output
+// slot from the offsets and its rank in the lane mask. Integer-only: bit-exact.
 #include "common.h"
 
 namespace audiokv {
@@ -63,18 +64,28 @@ __device__ __forceinline__ void block_exscan2(int a, int b, int* slots /* 2*kSel
 }
 
 constexpr int kCompact = 8;          // undecided keys per thread once the candidates have been narrowed down
+// Pivots from a sample: of 512 keys spread over the head, the two whose ranks lie kMargin on either side of the
+// budget's quantile bracket the threshold except with a probability of about 1e-4 (kMargin is 4 sigma of the binomial
+// spread of a 512-sample quantile) and hold about 2 * kMargin / 512 = 17 % of the keys between them (the short list
+// holds 25 % of the longest head: 4.7 sigma of the spread of that share).
+constexpr int kSamples = 512, kMargin = 44;
+constexpr int kPivotBits = 20;       // a pivot need not be a key: its low bits stay zero, which shortens the search for it
 
 template <int EPT>   // tokens per thread; the head must have at most EPT * kSelThreads candidates
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     Geom g, const float* __restrict__ scores, const int32_t* __restrict__ budgets,
     const int32_t* __restrict__ cu_b, const int32_t* __restrict__ cu_seq, int32_t* __restrict__ indices)
 {
-    extern __shared__ int32_t lds_out[];             // kept indices at their output slots (up to EPT*kSelThreads)
+    __shared__ uint32_t narrowed[kCompact * kSelThreads];   // keys still undecided after narrowing (any order)
     __shared__ int slots[4 * kSelWaves];
     __shared__ int pass_count[3];
-    __shared__ uint32_t gt_words[kSelThreads + 2], eq_words[kSelThreads + 2];   // one bit per token, 32 tokens per word
-    // keys still undecided after narrowing: in the output buffer, which is not needed before the threshold is known
-    uint32_t* narrowed = reinterpret_cast<uint32_t*>(lds_out);
+    __shared__ int list_n, last_n;                   // fill counts of `narrowed` and `last_keys`
+    __shared__ __attribute__((aligned(16))) uint32_t last_keys[64];
+    __shared__ uint32_t verdict[2];                  // threshold and #(key > threshold) from the wave that ranks the last keys
+    __shared__ int chunk_gt[EPT * kSelWaves], chunk_eq[EPT * kSelWaves];   // per (register, wave) chunk of 64 tokens
+    __shared__ uint32_t samp[kSamples];
+    __shared__ uint32_t pivot[2];
+    __shared__ int above_hi;
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
@@ -114,10 +125,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     // tell apart. Once they are few they are moved to a short list, kCompact per thread, and the remaining passes
     // count only those; the keys above the bracket are a constant.
     if (tid < 3) pass_count[tid] = 0;
+    if (tid == 3) { list_n = 0; last_n = 0; above_hi = 0; }
+    if (tid < 64) last_keys[tid] = 0u;               // 0 is below every key that can reach the list
     __syncthreads();
     uint32_t T = 0;
     int c_lo = n_cand, c_up = 0;
     int parity = 0;
+    // Move the keys for which `in_bracket` holds to the short list. Its order does not matter (the keys are only
+    // counted), so a wave reserves room for all its keys with one LDS add and places them by lane-mask rank.
+    auto to_short_list = [&](auto in_bracket) {
+        int wave_total = 0;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            wave_total += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in_bracket(key[e])));
+        int base = 0;
+        if (lane == 0 && wave_total) base = atomicAdd(&list_n, wave_total);
+        base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const bool in = in_bracket(key[e]);
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(in);
+            const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, (uint32_t)base));
+            if (in && pos < kCompact * kSelThreads) narrowed[pos] = key[e];   // keys beyond the list's end are dropped: the caller checks list_n
+            base += __builtin_popcountll(m);
+        }
+        __syncthreads();
+    };
     // One counting pass: `c` is this wave's count of keys >= trial (wave-uniform). The block-wide sum goes through
     // one LDS counter per pass (three in rotation: the counter of the next pass was last read two passes ago,
     // before the previous barrier, so it is cleared while this one is in use). Integer adds: order-free.
@@ -130,8 +163,75 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         parity = parity == 2 ? 0 : parity + 1;
     };
     int bit = 31;
+    bool have_list = false;
+    if (EPT > kCompact && n_cand >= 12 * kSelThreads) {
+        // Long head: instead of counting all keys once per bit until few are undecided, bracket the threshold between
+        // two pivots taken from a sample and go on with the keys in between. Whatever the sample looks like the result
+        // is exact: the counts are checked, and a bracket that misses the threshold or holds too many keys (heavy
+        // ties, adversarial order) falls back to the bit-by-bit passes.
+        const int full_regs = n_cand / kSelThreads;              // registers that hold a real key in every thread
+        {
+            // sample i: thread 2 i, a register that runs through [0, full_regs) in scrambled order
+            const int i = tid >> 1;
+            const int my_e = (((i * 97) & (kSamples - 1)) * full_regs) / kSamples;
+            uint32_t sk = 0;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) sk = e == my_e ? key[e] : sk;
+            if ((tid & 1) == 0) samp[i] = sk;
+        }
+        __syncthreads();
+        if (wave < 2) {
+            // Two waves find one pivot each, the sample of rank r (0 = largest) cut to its upper kPivotBits bits: the
+            // same bit-by-bit search as below, on 8 samples per lane and with no barrier (a wave is alone with its counts).
+            const int centre = (int)(((long long)want * kSamples) / n_cand);   // sample rank of the budget's quantile
+            const int r = wave == 0 ? centre - kMargin : centre + kMargin;
+            uint32_t sk[kSamples / 64];
+#pragma unroll
+            for (int j = 0; j < kSamples / 64; ++j) sk[j] = samp[lane + 64 * j];
+            uint32_t V = 0;
+            for (int bb = 31; bb >= 32 - kPivotBits; --bb) {
+                const uint32_t trial = V | (1u << bb);
+                int c = 0;
+#pragma unroll
+                for (int j = 0; j < kSamples / 64; ++j) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(sk[j] >= trial));
+                if (c > r) V = trial;                // r < 0: every trial passes: (almost) nothing is at or above V
+            }
+            if (lane == 0) pivot[1 - wave] = max(V, 1u);   // r >= kSamples: no trial passes; 1 is below every real key
+        }
+        __syncthreads();
+        const uint32_t lo = pivot[0], hi = pivot[1];                         // lo <= hi
+        {
+            // keys at or above hi are only counted (per lane, then summed over the wave through lane masks) ...
+            uint32_t per_lane = 0;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) per_lane += key[e] >= hi ? 1u : 0u;
+            int c_hi = 0;
+#pragma unroll
+            for (int bb = 0; EPT >> bb; ++bb)            // per_lane <= EPT
+                c_hi += __builtin_popcountll(__builtin_amdgcn_ballot_w64((per_lane >> bb) & 1u)) << bb;
+            if (lane == 0 && c_hi) atomicAdd(&above_hi, c_hi);
+        }
+        // ... and the keys in [lo, hi) go to the short list
+        to_short_list([&](uint32_t kx) { return kx - lo < hi - lo; });   // nothing if lo == hi
+        const int n_hi = above_hi, n_in = list_n;
+        if (lo < hi && n_hi < want && want <= n_hi + n_in && n_in <= kCompact * kSelThreads) {   // uniform
+            have_list = true;
+            // lo and hi - 1 agree above their highest differing bit d: those bits are the threshold's. Below, the
+            // short list alone decides: for a trial T' in that range #(key >= T') is n_hi plus the listed keys >= T'
+            // wherever that matters (a trial at or above hi must fail and does, one at or below lo must pass and does).
+            const uint32_t x = lo ^ (hi - 1u);
+            const int d = x ? 31 - __builtin_clz(x) : -1;
+            T = d >= 0 ? (lo & ~((2u << d) - 1u)) : lo;
+            bit = d + 1;                                 // the short passes start at bit d
+            c_lo = n_hi + n_in;
+            c_up = n_hi;
+        } else {
+            __syncthreads();                             // everybody has read list_n
+            if (tid == 0) list_n = 0;                    // (the bit-by-bit passes below meet at barriers before it is used again)
+        }
+    }
     bool narrow = false;
-    for (; bit >= 0; --bit) {
+    for (; !have_list && bit >= 0; --bit) {
         const uint32_t trial = T | (1u << bit);
         // Wave-wide count, split between the two issue ports so that neither is the bottleneck: the even registers
         // through lane masks and population counts on the scalar unit (which the whole CU shares), the odd ones
@@ -151,18 +251,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         if (EPT > kCompact && bit > 0 && (T >> bit) != 0u && c_lo - c_up <= kCompact * kSelThreads) { narrow = true; break; }
     }
     if (narrow) {
-        // move the real keys in [T, T + 2^bit) to the short list, kCompact per thread, evenly spread
+        // the real keys in [T, T + 2^bit): those whose upper bits equal T's
         const uint32_t hi_part = T >> bit;
-        int mine = 0;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) mine += (key[e] >> bit) == hi_part ? 1 : 0;
-        int before, unused;
-        block_exscan2(mine, 0, slots + 2 * kSelWaves, before, unused);
-#pragma unroll
-        for (int e = 0; e < EPT; ++e)
-            if ((key[e] >> bit) == hi_part) narrowed[before++] = key[e];
-        __syncthreads();
-        const int n_und = c_lo - c_up;
+        to_short_list([&](uint32_t kx) { return (kx >> bit) == hi_part; });
+        have_list = true;
+    }
+    if (have_list) {
+        const int n_und = c_lo - c_up;               // == list_n
         const int c_above = c_up;                    // keys above the bracket: counted in every later pass
         uint32_t ckey[kCompact];
 #pragma unroll
@@ -170,52 +265,97 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             const int i = tid + e * kSelThreads;
             ckey[e] = i < n_und ? narrowed[i] : 0u;
         }
+        bool rank_last = false;
         for (--bit; bit >= 0; --bit) {
             const uint32_t trial = T | (1u << bit);
             int c = 0;
 #pragma unroll
             for (int e = 0; e < kCompact; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ckey[e] >= trial));
             decide(trial, c, c_above);
+            if (bit > 0 && c_lo - c_up <= 64) { rank_last = true; break; }   // uniform
+        }
+        if (rank_last) {
+            // At most 64 keys share T's upper bits: the remaining bits of the threshold are those of the r-th largest
+            // of them, r = want - c_up. One wave holds them a key per lane and ranks each against all the others.
+            const uint32_t hi2 = T >> bit;
+            int wt = 0;
+#pragma unroll
+            for (int e = 0; e < kCompact; ++e)
+                wt += __builtin_popcountll(__builtin_amdgcn_ballot_w64((ckey[e] >> bit) == hi2));
+            int b2 = 0;
+            if (lane == 0 && wt) b2 = atomicAdd(&last_n, wt);
+            b2 = __builtin_amdgcn_readfirstlane(b2);
+#pragma unroll
+            for (int e = 0; e < kCompact; ++e) {
+                const bool in = (ckey[e] >> bit) == hi2;
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(in);
+                const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, (uint32_t)b2));
+                if (in && pos < 64) last_keys[pos] = ckey[e];
+                b2 += __builtin_popcountll(m);
+            }
+            __syncthreads();
+            if (wave == 0) {
+                const int n_last = c_lo - c_up;      // == last_n, 1..64; the rest of last_keys is 0
+                const uint32_t mine_k = last_keys[lane];
+                const int r = want - c_up;           // 1 <= r <= n_last
+                int gt = 0, ge = 0;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    const uint4 v = reinterpret_cast<const uint4*>(last_keys)[jj];
+                    gt += (v.x > mine_k ? 1 : 0) + (v.y > mine_k ? 1 : 0) + (v.z > mine_k ? 1 : 0) + (v.w > mine_k ? 1 : 0);
+                    ge += (v.x >= mine_k ? 1 : 0) + (v.y >= mine_k ? 1 : 0) + (v.z >= mine_k ? 1 : 0) + (v.w >= mine_k ? 1 : 0);
+                }
+                // the r-th largest value v has #(key > v) < r <= #(key >= v); every lane that holds v says so
+                const bool is_thr = lane < n_last && gt < r && r <= ge;
+                const unsigned long long who = __builtin_amdgcn_ballot_w64(is_thr);
+                const int first = __builtin_ctzll(who | (1ull << 63));
+                if (lane == first) { verdict[0] = mine_k; verdict[1] = (uint32_t)(c_up + gt); }
+            }
+            __syncthreads();
+            T = verdict[0];
+            c_up = (int)verdict[1];
         }
     }
     // tokens strictly above T all stay; tokens equal to T stay in index order while room is left
     const int need_eq = want - c_up;                 // c_up = #(key > T); >= 1 by construction of T
 
-    // per-token bitmaps of (key > T) and (key == T) from lane masks: wave w, register e covers tokens
-    // [e*1024 + w*64, +64)
+    // For a fixed register e, wave w holds the 64 consecutive tokens [e*1024 + w*64, +64): chunk e*16 + w in token
+    // order. Count the chunk's tokens above and equal to T from lane masks (lane e collects the counts of register e) ...
+    int my_gt = 0, my_eq = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const unsigned long long mg = __builtin_amdgcn_ballot_w64(key[e] > T);
-        const unsigned long long me = __builtin_amdgcn_ballot_w64(key[e] == T);
-        if (lane == 0) {
-            const int wd = (e * kSelThreads + wave * 64) >> 5;
-            gt_words[wd] = (uint32_t)mg; gt_words[wd + 1] = (uint32_t)(mg >> 32);
-            eq_words[wd] = (uint32_t)me; eq_words[wd + 1] = (uint32_t)(me >> 32);
-        }
+        const int cg = __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] > T));
+        const int ce = __builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] == T));
+        // lane e of my_gt / my_eq <- the wave-uniform counts of register e
+        asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(my_gt) : "s"(cg), "n"(e));
+        asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(my_eq) : "s"(ce), "n"(e));
+    }
+    if (lane < EPT) { chunk_gt[lane * kSelWaves + wave] = my_gt; chunk_eq[lane * kSelWaves + wave] = my_eq; }
+    __syncthreads();
+    // ... turn the counts into exclusive prefixes over the chunks (one scan for both) ...
+    {
+        constexpr int kChunks = EPT * kSelWaves;     // <= 512
+        const int a = tid < kChunks ? chunk_gt[tid] : 0, bq = tid < kChunks ? chunk_eq[tid] : 0;
+        int ea, eb;
+        block_exscan2(a, bq, slots + 2 * kSelWaves, ea, eb);
+        if (tid < kChunks) { chunk_gt[tid] = ea; chunk_eq[tid] = eb; }
     }
     __syncthreads();
-    // thread t now owns tokens [32t, 32t + 32): ascending output slots through one block-wide exclusive scan
-    uint32_t mg = 0, me = 0;
-    if (tid < EPT * (kSelThreads / 32)) { mg = gt_words[tid]; me = eq_words[tid]; }
-    int gt_before, eq_before;
-    block_exscan2(__builtin_popcount(mg), __builtin_popcount(me), slots + 2 * kSelWaves, gt_before, eq_before);
-    // Kept indices are gathered in LDS at their output slots and then written out in one coalesced sweep; written
-    // straight from here, every store of a wave would touch 64 different cache lines.
-    uint32_t m = mg | me;
-    while (m) {
-        const int bpos = __builtin_ctz(m);
-        m &= m - 1;
-        const int j = tid * 32 + bpos;
-        if ((mg >> bpos) & 1u) {
-            lds_out[gt_before + min(eq_before, need_eq)] = j;
-            ++gt_before;
-        } else {
-            if (eq_before < need_eq) lds_out[gt_before + eq_before] = j;
-            ++eq_before;
-        }
+    // ... and let every kept token compute its output slot: tokens above T before it, plus the kept ties before it.
+    // The slots of a wave's tokens are consecutive, so each store instruction writes one run of the output.
+    if (lane < EPT) { my_gt = chunk_gt[lane * kSelWaves + wave]; my_eq = chunk_eq[lane * kSelWaves + wave]; }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const bool is_gt = key[e] > T, is_eq = key[e] == T;
+        const unsigned long long mg = __builtin_amdgcn_ballot_w64(is_gt);
+        const unsigned long long me = __builtin_amdgcn_ballot_w64(is_eq);
+        const int gt_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32),
+                                  __builtin_amdgcn_mbcnt_lo((uint32_t)mg, (uint32_t)__builtin_amdgcn_readlane(my_gt, e)));
+        const int eq_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32),
+                                  __builtin_amdgcn_mbcnt_lo((uint32_t)me, (uint32_t)__builtin_amdgcn_readlane(my_eq, e)));
+        const int pos = gt_before + min(eq_before, need_eq);
+        if ((is_gt || (is_eq && eq_before < need_eq)) && pos < want) out[pos] = tid + e * kSelThreads;
     }
-    __syncthreads();
-    for (int t = tid; t < want; t += kSelThreads) out[t] = lds_out[t];
 }
 
 // Heads longer than 32 * 1024 tokens: the keys do not fit the registers of one workgroup, so every counting pass
@@ -362,16 +502,7 @@ hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budg
     const int ept_needed = (max_L + kSelThreads - 1) / kSelThreads;
 #define AUDIOKV_LAUNCH_SELECT(E)                                                                        \
     do {                                                                                                \
-        const size_t n = (size_t)(E) * kSelThreads;                                                     \
-        const size_t smem = n * sizeof(int32_t);                                                        \
-        static std::atomic<bool> attr_set{false};                                                                   \
-        if (!attr_set && smem > 48 * 1024) {                                                            \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<E>),         \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);  \
-            if (e != hipSuccess) return e;                                                              \
-            attr_set = true;                                                                            \
-        }                                                                                               \
-        hipLaunchKernelGGL((select_kernel<E>), dim3(n_heads), dim3(kSelThreads), smem, s, g, scores,    \
+        hipLaunchKernelGGL((select_kernel<E>), dim3(n_heads), dim3(kSelThreads), 0, s, g, scores,       \
                            budgets, cu_budgets, cu_seqlens, indices);                                   \
     } while (0)
     if (ept_needed <= 4) AUDIOKV_LAUNCH_SELECT(4);

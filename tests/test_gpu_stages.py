@@ -158,6 +158,24 @@ def test_select_adversarial(A):
     _select_case(A, [const, ramp, neg, ramp[::-1].copy()], [L], 4, [W, W + 1, L - 1, 77], W)   # b = W: window only
 
 
+@pytest.mark.parametrize("L,W", [(12352, 64), (16384, 32), (30000, 1), (32768, 64)])
+def test_select_long_heads_every_distribution(A, L, W):
+    """Long heads bracket the threshold between two pivots taken from a sample of the keys; the result must not depend
+    on how good the sample is. Distributions that defeat it (sorted, periodic in the register layout, alternating with
+    the sampled threads, plateaus, few distinct values, a narrow range, half zeros) and budgets at both extremes."""
+    rng = np.random.default_rng(L + W)
+    x = rng.standard_normal(L)
+    t = np.arange(L)
+    dists = [x, np.exp(3 * x), np.sort(x), np.sort(x)[::-1], np.round(x * 2) / 2, np.full(L, 0.5),
+             np.sin(t * 2 * np.pi / 1024) + 1e-3 * x, (t % 2) * 100.0 + x, 1.0 + 1e-5 * x,
+             np.where(rng.random(L) < 0.5, 0.0, np.abs(x)), -np.exp(x)]
+    heads = [np.ascontiguousarray(s, dtype=np.float32) for s in dists]
+    lo = max(W, 1)
+    for budgets in ([int(rng.integers(lo, L + 1)) for _ in heads], [int(0.4 * L)] * len(heads),
+                    [lo + 3] * len(heads), [L - 5] * len(heads)):
+        _select_case(A, heads, [L], len(heads), budgets, W)
+
+
 def test_select_ragged_items(A):
     rng = np.random.default_rng(9)
     lens = [100, 2500, 33]
