@@ -133,7 +133,7 @@ Workspace plan_workspace(const audiokv_params* p, const Batch& b, const int32_t*
     const int n_heads = b.n_items * p->n_kv_heads;
     const int rows = (p->n_q_heads / p->n_kv_heads) * (p->window > 0 ? p->window : 1);
     const int rows_pad = score_padded_rows(rows, p->head_dim);
-    const int nsplit = score_num_splits(n_heads, b.max_L, rows, p->head_dim);
+    const int nsplit = score_num_splits(p->n_kv_heads, b.n_items, seqlens_host, rows, p->head_dim);
     size_t off = 0;
     w.stats_off = off;
     // partial row statistics [head][split][rows_pad][2], then the merged per-row constants [head][rows_pad]
@@ -284,7 +284,7 @@ int32_t score_entry(const audiokv_params* params, const void* q_win, const void*
     char* ws = static_cast<char*>(workspace);
     float* stats = reinterpret_cast<float*>(ws + w.stats_off);
     float* raw = params->pool_kernel == 1 ? scores : reinterpret_cast<float*>(ws + w.raw_off);
-    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s, nullptr, lse_dev,
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, seqlens_host, stats, raw, s, nullptr, lse_dev,
                              w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
                              (size_t)b.total_tokens * params->n_kv_heads), "score kernels");
     if (params->pool_kernel != 1)
@@ -512,7 +512,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
         AUDIOKV_HIP(hipEventRecord(g_helper.join, g_helper.stream), "hipEventRecord");
     }
     AUDIOKV_MARK(1);
-    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, b.max_L, stats, raw, s,
+    AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, seqlens_host, stats, raw, s,
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev,
                              w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
                              (size_t)b.total_tokens * params->n_kv_heads), "score kernels");

@@ -47,14 +47,14 @@ __device__ __forceinline__ int64_t kv_row_offset(const Geom& g, int item, int64_
 
 // Number of key-range splits per head used by the score kernels; a pure
 // function of the batch so that the workspace query and the launch agree.
-int score_num_splits(int n_heads_total, int max_L, int rows, int D);
+int score_num_splits(int H_kv, int n_items, const int32_t* seqlens_host, int rows, int D);
 // Padded row count (multiple of the MFMA row tiling) for G*W window rows; 0 if unsupported.
 int score_padded_rows(int rows, int D);
 
 // between_sweeps: optional event recorded on `s` after the first sweep (timing aid), or nullptr.
 // lse: optional fp32 [items][H_q][W] natural-log softmax denominators of the window rows; given, sweep 1 is skipped.
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
-                        int max_L, float* stats_ws, float* raw_out, hipStream_t s,
+                        const int32_t* seqlens_host, float* stats_ws, float* raw_out, hipStream_t s,
                         hipEvent_t between_sweeps = nullptr, const float* lse = nullptr,
                         float* raw_second = nullptr, size_t raw_elems = 0);
 // More than 448 window rows (d <= 128): sweep 2 runs as two launches and needs a second buffer of the size of the

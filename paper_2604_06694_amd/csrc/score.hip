@@ -32,22 +32,52 @@ bool make_plan(int rows, int D, int sweep, Plan* out) {
     return false;
 }
 
-int num_splits(const Plan& p, int n_heads_total, int max_L, int D) {
-    // A head is cut into key ranges so that the grid fills the 256 CUs in whole rounds: pick the split
-    // count that minimises rounds x (tiles per workgroup + fixed prologue cost, in tiles).
-    const int tiles = (max_L + p.tile_keys - 1) / p.tile_keys;
+int num_splits(const Plan& p, int H_kv, int n_items, const int32_t* seqlens_host, int D) {
+    // A head is cut into key ranges so that the grid fills the 256 CUs evenly: the split count minimises the time of
+    // the launch in units of one tile, with a fixed prologue cost per workgroup (in tiles).
     // resident workgroups per CU: two when the waves are few or hold one row tile each (128 registers), or when
     // the workgroup is four waves of three row tiles; one when eight waves take all the registers
     const bool two = (p.NB == 1 && D <= 128) || p.WR < 4 || (p.NB == 3 && p.WR == 3);
     const int slots = 256 * (two ? 2 : 1);
-    const int overhead = 3;
+    // what a workgroup costs before its first and after its last tile (query fragments, filling the ring, the row
+    // statistics or constants), in tiles: about 200 keys' worth, fitted to measured launches
+    const int overhead = p.tile_keys >= 64 ? 3 : 7;
+    int max_tiles = 1;
+    bool uniform = true;
+    for (int i = 0; i < n_items; ++i) {
+        const int t = (seqlens_host[i] + p.tile_keys - 1) / p.tile_keys;
+        if (t > max_tiles) max_tiles = t;
+        if (seqlens_host[i] != seqlens_host[0]) uniform = false;
+    }
     int best = 1;
     long long best_cost = -1;
-    const int ns_max = tiles < 64 ? tiles : 64;
+    const int ns_max = max_tiles < 64 ? max_tiles : 64;
     for (int ns = 1; ns <= ns_max; ++ns) {
-        const long long groups = (long long)n_heads_total * ns;
-        const long long rounds = (groups + slots - 1) / slots;
-        const long long cost = rounds * ((tiles + ns - 1) / ns + overhead);
+        long long cost;
+        if (uniform) {
+            // equal workgroups run in whole rounds
+            const long long groups = (long long)n_items * H_kv * ns;
+            const long long rounds = (groups + slots - 1) / slots;
+            cost = rounds * ((max_tiles + ns - 1) / ns + overhead);
+        } else {
+            // Ragged lengths: a head's ranges are as long as the head is (tiles of the head / ns), and workgroups
+            // start as others end. The launch takes about the average load of a slot, plus part of the longest
+            // workgroup for the ones that start last, plus, when the last round of workgroups fills only part of the
+            // slots, that round's average workgroup for the slots left idle (all in twice the unit, to keep halves).
+            long long total = 0, longest = 0;
+            const long long groups = (long long)n_items * H_kv * ns;   // launched, whether or not they hold tiles
+            for (int i = 0; i < n_items; ++i) {
+                const int t = (seqlens_host[i] + p.tile_keys - 1) / p.tile_keys;
+                if (t <= 0) continue;
+                const int tps = (t + ns - 1) / ns;
+                const int used = (t + tps - 1) / tps;          // ranges of this head that hold tiles
+                total += (long long)H_kv * (t + (long long)used * overhead);
+                if (tps + overhead > longest) longest = tps + overhead;
+            }
+            cost = 2 * ((total + slots - 1) / slots) + longest;
+            const long long rem = groups % slots;
+            if (groups > slots && rem) cost += 2 * (total / groups) * (slots - rem) / slots;
+        }
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = ns; }
     }
     return best;
@@ -77,14 +107,14 @@ int score_padded_rows(int rows, int D) {
 bool score_needs_second_raw(int rows, int D) { return sweep2_is_split(rows, D); }
 
 // key ranges per head of sweep 1: what sizes the statistics in the workspace
-int score_num_splits(int n_heads_total, int max_L, int rows, int D) {
+int score_num_splits(int H_kv, int n_items, const int32_t* seqlens_host, int rows, int D) {
     Plan p;
-    if (!make_plan(rows, D, 1, &p) || n_heads_total <= 0) return 1;
-    return num_splits(p, n_heads_total, max_L, D);
+    if (!make_plan(rows, D, 1, &p) || n_items <= 0 || H_kv <= 0) return 1;
+    return num_splits(p, H_kv, n_items, seqlens_host, D);
 }
 
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
-                        int max_L, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
+                        const int32_t* seqlens_host, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
                         const float* lse, float* raw_second, size_t raw_elems)
 {
     Plan p1;
@@ -93,7 +123,7 @@ hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const i
     const int n_heads = g.n_items * g.H_kv;
     const int rows_pad = score_padded_rows(rows, g.D);
     if (rows_pad == 0) return hipErrorInvalidValue;
-    const int ns1 = num_splits(p1, n_heads, max_L, g.D);
+    const int ns1 = num_splits(p1, g.H_kv, g.n_items, seqlens_host, g.D);
     float* cst = stats_ws + (size_t)n_heads * ns1 * rows_pad * 2;
     auto sweep = [&](int which, const Plan& p, int ns, int row_base, float* raw) -> hipError_t {
         switch (g.D) {
@@ -112,14 +142,14 @@ hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const i
     Plan p2;
     if (!sweep2_is_split(rows, g.D)) {
         if (!make_plan(rows, g.D, 2, &p2)) return hipErrorInvalidValue;
-        return sweep(2, p2, num_splits(p2, n_heads, max_L, g.D), 0, raw_out);
+        return sweep(2, p2, num_splits(p2, g.H_kv, g.n_items, seqlens_host, g.D), 0, raw_out);
     }
     if (!raw_second) return hipErrorInvalidValue;
     Plan p2b;
     if (!make_plan(kSweep2MaxRows, g.D, 2, &p2) || !make_plan(rows - kSweep2MaxRows, g.D, 2, &p2b)) return hipErrorInvalidValue;
-    e = sweep(2, p2, num_splits(p2, n_heads, max_L, g.D), 0, raw_out);
+    e = sweep(2, p2, num_splits(p2, g.H_kv, g.n_items, seqlens_host, g.D), 0, raw_out);
     if (e != hipSuccess) return e;
-    e = sweep(2, p2b, num_splits(p2b, n_heads, max_L, g.D), kSweep2MaxRows, raw_second);
+    e = sweep(2, p2b, num_splits(p2b, g.H_kv, g.n_items, seqlens_host, g.D), kSweep2MaxRows, raw_second);
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)((raw_elems + 256 * 8 - 1) / (256 * 8));
     hipLaunchKernelGGL(score_detail::score_add_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, s, raw_out,
