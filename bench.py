@@ -185,6 +185,10 @@ def time_config(A, cfg, data, steps, warmup, dev):
         key = {"compact": "compact", "pool_smooth": "scores_rw", "select": "indices_rw", "allocate": "indices_rw"}[dominant]
         roof = {"bound": "hbm", "achieved": ab[key] / dom_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "kernel": dominant, "kernel_ms": stage_ms[dominant], "traffic": None}
+        if dominant != "compact":
+            roof["note"] = ("a chain of small per-head kernels, bound by launch and barrier latency rather than by bandwidth; "
+                            "with stage timing on, work that otherwise runs beside the score sweeps on the helper stream "
+                            "(chirp-z filter preparation for lengths that are not powers of two) is in line and counted here")
     roof["frac"] = roof["achieved"] / roof["peak"]
     return {"dt": dt, "stage_ms": stage_ms, "tokens": tokens, "kept": kept, "ab": ab, "score_flops": score_flops,
             "roof": roof, "p": p, "scope": scope, "cu": cu, "ws": ws, "outs": outs, "step": step}
@@ -202,6 +206,8 @@ def other_config_line(A, index, steps, warmup, dev, **over):
             "stage_ms": {n: round(x, 4) for n, x in m["stage_ms"].items()},
             "dominant": {"kernel": m["roof"]["kernel"], "bound": m["roof"]["bound"], "frac": m["roof"]["frac"],
                          "hbm_GBs_of_this_kernel": m["roof"].get("hbm_GBs_of_this_kernel")}}
+    if "note" in m["roof"]:
+        line["dominant"]["note"] = m["roof"]["note"]
     del data, m
     torch.cuda.empty_cache()
     return line
