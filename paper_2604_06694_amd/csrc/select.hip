@@ -86,6 +86,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ uint32_t samp[kSamples];
     __shared__ uint32_t pivot[2];
     __shared__ int above_hi;
+    __shared__ __attribute__((aligned(16))) int hist[256];   // digit counts of the short list
+    __shared__ int digit_verdict[3];
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
@@ -127,6 +129,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     if (tid < 3) pass_count[tid] = 0;
     if (tid == 3) { list_n = 0; last_n = 0; above_hi = 0; }
     if (tid < 64) last_keys[tid] = 0u;               // 0 is below every key that can reach the list
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     uint32_t T = 0;
     int c_lo = n_cand, c_up = 0;
@@ -163,7 +166,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         parity = parity == 2 ? 0 : parity + 1;
     };
     int bit = 31;
-    bool have_list = false;
+    // Heads of at most kCompact keys per thread are their own short list from the start (all 32 bits undecided).
+    bool have_list = EPT <= kCompact;
+    bool spread = false;                             // the listed keys lie between two pivots: no crowded digits
+    if (EPT <= kCompact) bit = 32;
     if (EPT > kCompact && n_cand >= 12 * kSelThreads) {
         // Long head: instead of counting all keys once per bit until few are undecided, bracket the threshold between
         // two pivots taken from a sample and go on with the keys in between. Whatever the sample looks like the result
@@ -216,6 +222,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         const int n_hi = above_hi, n_in = list_n;
         if (lo < hi && n_hi < want && want <= n_hi + n_in && n_in <= kCompact * kSelThreads) {   // uniform
             have_list = true;
+            spread = true;
             // lo and hi - 1 agree above their highest differing bit d: those bits are the threshold's. Below, the
             // short list alone decides: for a trial T' in that range #(key >= T') is n_hi plus the listed keys >= T'
             // wherever that matters (a trial at or above hi must fail and does, one at or below lo must pass and does).
@@ -263,16 +270,59 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
         for (int e = 0; e < kCompact; ++e) {
             const int i = tid + e * kSelThreads;
-            ckey[e] = i < n_und ? narrowed[i] : 0u;
+            if constexpr (EPT <= kCompact) ckey[e] = e < EPT ? key[e < EPT ? e : 0] : 0u;   // (0 where there is no token)
+            else ckey[e] = i < n_und ? narrowed[i] : 0u;
         }
+        // (validity of a listed key is its index, tid + e * 1024 < n_und, in both cases: the value 0 also passes for
+        // a key whose upper bits equal T's when those are all zero)
+        // Undecided bits are [0, bit - 1]. They are settled one per pass while they are exponent bits of keys that
+        // may crowd into a few digits, and eight per round otherwise (bits 22 and lower, or any bits of keys that lie
+        // between two pivots: LDS adds to one address serialise, adds spread over the digits do not): the listed keys whose
+        // upper bits equal T's are counted by their next eight bits in LDS (integer adds), and one wave finds the
+        // largest digit D with c_up + #(digit >= D) >= want from the suffix sums: what eight passes would set.
+        // As soon as at most 64 keys are undecided, one wave ranks them (below).
         bool rank_last = false;
-        for (--bit; bit >= 0; --bit) {
+        while (bit > 0) {
+            if (bit <= 31 && c_lo - c_up <= 64) { rank_last = true; break; }   // uniform
+            if (bit >= 8 && bit <= (spread ? 31 : 23)) {
+                const int sh = bit - 8;
+                const uint32_t prefix = T >> bit;
+#pragma unroll
+                for (int e = 0; e < kCompact; ++e)
+                    if (tid + e * kSelThreads < n_und && (ckey[e] >> bit) == prefix)
+                        atomicAdd(&hist[(ckey[e] >> sh) & 255u], 1);
+                __syncthreads();
+                if (wave == 0) {
+                    const int4 h4 = reinterpret_cast<const int4*>(hist)[lane];          // digits 4 lane .. 4 lane + 3
+                    const int s3 = h4.w, s2 = s3 + h4.z, s1 = s2 + h4.y, s0 = s1 + h4.x;   // sums up to the lane's last digit
+                    int incl = s0;                                                     // + all higher lanes
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const int t = __shfl_down(incl, o, 64);
+                        if (lane + o < 64) incl += t;
+                    }
+                    const int base = c_up + incl - s0;       // keys above the bracket + digits above this lane's
+                    const int S[5] = {base + s0, base + s1, base + s2, base + s3, base};   // #(key >= T | D << sh), D = 4 lane + K
+#pragma unroll
+                    for (int K = 0; K < 4; ++K)
+                        if (S[K] >= want && S[K + 1] < want) {   // exactly one (lane, K): S falls from c_lo >= want to c_up < want
+                            digit_verdict[0] = 4 * lane + K; digit_verdict[1] = S[K]; digit_verdict[2] = S[K + 1];
+                        }
+                    reinterpret_cast<int4*>(hist)[lane] = make_int4(0, 0, 0, 0);        // for the next round
+                }
+                __syncthreads();
+                T |= (uint32_t)digit_verdict[0] << sh;
+                c_lo = digit_verdict[1];
+                c_up = digit_verdict[2];
+                bit = sh;
+                continue;
+            }
+            --bit;
             const uint32_t trial = T | (1u << bit);
             int c = 0;
 #pragma unroll
             for (int e = 0; e < kCompact; ++e) c += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ckey[e] >= trial));
             decide(trial, c, c_above);
-            if (bit > 0 && c_lo - c_up <= 64) { rank_last = true; break; }   // uniform
         }
         if (rank_last) {
             // At most 64 keys share T's upper bits: the remaining bits of the threshold are those of the r-th largest
@@ -281,13 +331,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             int wt = 0;
 #pragma unroll
             for (int e = 0; e < kCompact; ++e)
-                wt += __builtin_popcountll(__builtin_amdgcn_ballot_w64((ckey[e] >> bit) == hi2));
+                wt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(tid + e * kSelThreads < n_und && (ckey[e] >> bit) == hi2));
             int b2 = 0;
             if (lane == 0 && wt) b2 = atomicAdd(&last_n, wt);
             b2 = __builtin_amdgcn_readfirstlane(b2);
 #pragma unroll
             for (int e = 0; e < kCompact; ++e) {
-                const bool in = (ckey[e] >> bit) == hi2;
+                const bool in = tid + e * kSelThreads < n_und && (ckey[e] >> bit) == hi2;
                 const unsigned long long m = __builtin_amdgcn_ballot_w64(in);
                 const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, (uint32_t)b2));
                 if (in && pos < 64) last_keys[pos] = ckey[e];
@@ -506,6 +556,7 @@ hipError_t launch_select(const Geom& g, const float* scores, const int32_t* budg
                            budgets, cu_budgets, cu_seqlens, indices);                                   \
     } while (0)
     if (ept_needed <= 4) AUDIOKV_LAUNCH_SELECT(4);
+    else if (ept_needed <= 8) AUDIOKV_LAUNCH_SELECT(8);
     else if (ept_needed <= 16) AUDIOKV_LAUNCH_SELECT(16);
     else if (ept_needed <= 32) AUDIOKV_LAUNCH_SELECT(32);
     else   // longer heads than the registers and the LDS staging of one workgroup hold
