@@ -520,7 +520,7 @@ __device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
 
 // ------------------------ power-of-two lengths, few heads: one head on several workgroups ------------------------
 // A call with few heads (one layer of a prefill: four) leaves all but a handful of CUs idle while each head's
-// transform runs in one workgroup. For those calls a head of L = 2^p >= 1024 samples is cut into D = 16 interleaved
+// transform runs in one workgroup. For those calls a head of L = 2^p >= 16384 samples is cut into D = 16 interleaved
 // sub-sequences x_{16 m + r} of M = L / 16 samples, the first stage of a decimation-in-time FFT taken out of the
 // workgroup:
 //   dec_forward   per pair (r, r + 1): one complex M-point FFT in LDS gives the spectra G_r, G_{r+1} of the two
@@ -534,7 +534,7 @@ __device__ __forceinline__ void fill_tables(cf* lo, cf* hi, int n_hi, int M) {
 // in one place first.
 constexpr int kDecLog = 4, kDec = 1 << kDecLog;      // D
 constexpr int kDecThreads = 1024;    // the strided (and, inside evict, pooled) loads want many waves in flight
-constexpr int kDecMinL = 1024;
+constexpr int kDecMinL = 16384;   // below this one workgroup per head is as fast (measured: 8192 19 us alone, 21 us spread; 16384 33 and 21)
 constexpr int kDecMaxHeads = 64;                     // beyond this the heads fill the chip by themselves
 
 __host__ __device__ inline bool dec_length(int L) { return pow2_length(L) && L >= kDecMinL; }

@@ -233,7 +233,7 @@ def test_evict_energy_cutoff_on_ragged_lengths(A):
             off += L
 
 
-@pytest.mark.parametrize("L", [1024, 4096, 32768])
+@pytest.mark.parametrize("L", [4096, 16384, 32768])      # the few-heads path starts at 16384: below, both calls take one workgroup per head
 @pytest.mark.parametrize("cutoff,alpha,T", [(0.125, 1.0, 0), (0.25, 0.5, 0), (0.0625, 1.0, 9), (0.9, 1.0, 0), (0.0, 1.0, 0)])
 def test_few_heads_path_matches_one_workgroup_per_head_and_the_oracle(A, L, cutoff, alpha, T):
     """A call with few heads spreads every power-of-two head over several workgroups (interleaved sub-sequences);
