@@ -81,13 +81,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ int pass_count[3];
     __shared__ int list_n, last_n;                   // fill counts of `narrowed` and `last_keys`
     __shared__ __attribute__((aligned(16))) uint32_t last_keys[64];
-    __shared__ uint32_t verdict[2];                  // threshold and #(key > threshold) from the wave that ranks the last keys
+    __shared__ uint32_t ranked[2];                  // threshold and #(key > threshold) from the wave that ranks the last keys
     __shared__ int chunk_gt[EPT * kSelWaves], chunk_eq[EPT * kSelWaves];   // per (register, wave) chunk of 64 tokens
     __shared__ uint32_t samp[kSamples];
     __shared__ uint32_t pivot[2];
     __shared__ int above_hi;
     __shared__ __attribute__((aligned(16))) int hist[256];   // digit counts of the short list
-    __shared__ int digit_verdict[3];
+    __shared__ int digit_pick[3];
     const int head = blockIdx.x;
     const int item = head / g.H_kv, h = head - item * g.H_kv;
     const int tok0 = cu_seq[item];
@@ -306,14 +306,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
                     for (int K = 0; K < 4; ++K)
                         if (S[K] >= want && S[K + 1] < want) {   // exactly one (lane, K): S falls from c_lo >= want to c_up < want
-                            digit_verdict[0] = 4 * lane + K; digit_verdict[1] = S[K]; digit_verdict[2] = S[K + 1];
+                            digit_pick[0] = 4 * lane + K; digit_pick[1] = S[K]; digit_pick[2] = S[K + 1];
                         }
                     reinterpret_cast<int4*>(hist)[lane] = make_int4(0, 0, 0, 0);        // for the next round
                 }
                 __syncthreads();
-                T |= (uint32_t)digit_verdict[0] << sh;
-                c_lo = digit_verdict[1];
-                c_up = digit_verdict[2];
+                T |= (uint32_t)digit_pick[0] << sh;
+                c_lo = digit_pick[1];
+                c_up = digit_pick[2];
                 bit = sh;
                 continue;
             }
@@ -359,11 +359,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
                 const bool is_thr = lane < n_last && gt < r && r <= ge;
                 const unsigned long long who = __builtin_amdgcn_ballot_w64(is_thr);
                 const int first = __builtin_ctzll(who | (1ull << 63));
-                if (lane == first) { verdict[0] = mine_k; verdict[1] = (uint32_t)(c_up + gt); }
+                if (lane == first) { ranked[0] = mine_k; ranked[1] = (uint32_t)(c_up + gt); }
             }
             __syncthreads();
-            T = verdict[0];
-            c_up = (int)verdict[1];
+            T = ranked[0];
+            c_up = (int)ranked[1];
         }
     }
     // tokens strictly above T all stay; tokens equal to T stay in index order while room is left
