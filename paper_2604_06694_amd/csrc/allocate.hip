@@ -79,30 +79,30 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
     // proportional shares with the cap: heads over the cap are fixed at it and
     // the rest of the budget is shared again among the others
     for (;;) {
-        if (tid < 64) {
-            // In-order float64 sum of the free heads' weights. The order is fixed (head 0, 1, 2, ...), so the adds
-            // are serial, but the operands are staged 64 at a time in the lanes of one wave and read back with
-            // readlane, instead of one LDS round trip per head from a single thread.
-            int ncap = 0, nfree = 0;
+        // In-order float64 sum of the free heads' weights. The order is fixed (head 0, 1, 2, ...), so the adds form
+        // one serial chain, kept as short as it can be: all threads first stage the addends (a capped head adds
+        // +0.0, which leaves the sum as it is bit for bit; `frac` is free until the floors are taken) and count
+        // the capped heads, then one thread adds them up, fetching sixteen at a time.
+        long long my_cap = 0;
+        for (int h = tid; h < n; h += kThreads) {
+            const bool capped = (flag[h] & 1) != 0;
+            frac[h] = capped ? 0.0 : S[h];
+            my_cap += capped ? 1 : 0;
+        }
+        const int ncap = (int)block_sum_ll(my_cap, red);    // (its barriers also publish the addends)
+        if (tid == 0) {
+            constexpr int kBatch = 16;
             double tot = 0.0;
-            for (int base = 0; base < n; base += 64) {
-                const int h = base + tid;
-                const double sv = h < n ? S[h] : 0.0;
-                const int fv = h < n ? flag[h] : 0;
-                const int cnt = min(64, n - base);
-                for (int j = 0; j < cnt; ++j) {
-                    const int lo = __builtin_amdgcn_readlane(__double2loint(sv), j);
-                    const int hi = __builtin_amdgcn_readlane(__double2hiint(sv), j);
-                    const int fj = __builtin_amdgcn_readlane(fv, j);
-                    if (fj & 1) ++ncap;
-                    else { tot = __dadd_rn(tot, __hiloint2double(hi, lo)); ++nfree; }
-                }
+            for (int base = 0; base < n; base += kBatch) {
+                double av[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) av[u] = frac[min(base + u, n - 1)];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) tot = __dadd_rn(tot, base + u < n ? av[u] : 0.0);
             }
-            if (tid == 0) {
-                sh->tot = tot;
-                sh->n_free = nfree;
-                sh->T = (double)(Bs - (long long)ncap * cap);
-            }
+            sh->tot = tot;
+            sh->n_free = n - ncap;
+            sh->T = (double)(Bs - (long long)ncap * cap);
         }
         __syncthreads();
         const double tot = sh->tot, T = sh->T;
@@ -146,9 +146,12 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
         if (left == 0) break;
         const bool give = left > 0;
         const long long want = give ? left : -left;
+        // eligible heads compete with their fractional parts; the others get a value that is never ahead of anyone
+        // (`x` is free once the floors are taken)
         for (int h = tid; h < n; h += kThreads) {
             const bool el = !(flag[h] & 1) && (give ? e[h] < cap : e[h] > 0);
             flag[h] = (flag[h] & 1) | (el ? 2 : 0);
+            x[h] = el ? frac[h] : (give ? -1.0 : 2.0);
         }
         if (tid == 0) sh->granted = 0;
         __syncthreads();
@@ -157,12 +160,19 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
             if (!(flag[h] & 2)) continue;
             const double fh = frac[h];
             long long rank = 0;
-            for (int o = 0; o < n; ++o) {
-                if (!(flag[o] & 2)) continue;
-                const double fo = frac[o];
-                const bool ahead = give ? (fo > fh || (fo == fh && o < h))
-                                        : (fo < fh || (fo == fh && o > h));
-                rank += ahead ? 1 : 0;
+            // (the other heads' values sixteen at a time: one LDS latency per batch instead of one per head)
+            constexpr int kBatch = 16;
+            for (int base = 0; base < n; base += kBatch) {
+                double fo[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) fo[u] = x[min(base + u, n - 1)];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const int o = base + u;
+                    const bool ahead = give ? (fo[u] > fh || (fo[u] == fh && o < h))
+                                            : (fo[u] < fh || (fo[u] == fh && o > h));
+                    rank += (o < n && ahead) ? 1 : 0;
+                }
             }
             if (rank < want) { e[h] += give ? 1 : -1; ++my_granted; }
         }
