@@ -3,16 +3,21 @@
 //
 // One workgroup per head. Scores become order-preserving 32-bit keys held in
 // registers (token t + 1024 e in register e of thread t: coalesced loads).
-// The value of the k-th largest key is found bit by bit (32 counting passes,
-// no atomics); once the keys that the remaining bits can still separate are
-// few, they are moved to a short list and only they are counted; once at most
-// 64 are left, one wave ranks them against each other and reads the threshold
-// off directly. Tokens above the threshold are kept, tokens equal to it are
-// kept in index order until the budget is full: for a fixed register the lanes
-// of a wave hold 64 consecutive tokens, so lane masks give every (register,
-// wave) chunk its counts, one block-wide exclusive scan over the chunks gives
-// their output offsets, and every kept token computes its own ascending output
-// slot from the offsets and its rank in the lane mask. Integer-only: bit-exact.
+// The threshold is the largest T with #(key >= T) >= the number of tokens to
+// keep. A long head first brackets it between two pivots taken from a sample
+// of its keys and checks the counts (exact whatever the sample; a bracket that
+// fails falls back); otherwise T is found bit by bit with counting passes over
+// all keys until the keys that the remaining bits can still separate are few.
+// Those go to a short list in LDS (a short head is its own list), where the
+// remaining bits are set one per pass or eight per round (digit counts), and
+// once at most 64 keys are undecided one wave ranks them against each other
+// and reads the threshold off directly. Tokens above the threshold are kept,
+// tokens equal to it are kept in index order until the budget is full: for a
+// fixed register the lanes of a wave hold 64 consecutive tokens, so lane masks
+// give every (register, wave) chunk its counts, one block-wide exclusive scan
+// over the chunks gives their output offsets, and every kept token computes
+// its own ascending output slot from the offsets and its rank in the lane
+// mask. Integer-only (counts and integer adds in any order): bit-exact.
 #include "common.h"
 
 namespace audiokv {
