@@ -404,12 +404,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         const bool is_gt = key[e] > T, is_eq = key[e] == T;
         const unsigned long long mg = __builtin_amdgcn_ballot_w64(is_gt);
         const unsigned long long me = __builtin_amdgcn_ballot_w64(is_eq);
-        const int gt_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32),
-                                  __builtin_amdgcn_mbcnt_lo((uint32_t)mg, (uint32_t)__builtin_amdgcn_readlane(my_gt, e)));
-        const int eq_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32),
-                                  __builtin_amdgcn_mbcnt_lo((uint32_t)me, (uint32_t)__builtin_amdgcn_readlane(my_eq, e)));
-        const int pos = gt_before + min(eq_before, need_eq);
-        if ((is_gt || (is_eq && eq_before < need_eq)) && pos < want) out[pos] = tid + e * kSelThreads;
+        const int gt_pre = __builtin_amdgcn_readlane(my_gt, e), eq_pre = __builtin_amdgcn_readlane(my_eq, e);
+        if (me == 0) {
+            // no tie with the threshold among the chunk's 64 tokens (the usual case): the kept ties before any of
+            // them are a chunk-wide number, folded into the base of the lane-mask rank
+            const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32),
+                                __builtin_amdgcn_mbcnt_lo((uint32_t)mg, (uint32_t)(gt_pre + min(eq_pre, need_eq))));
+            if (is_gt && pos < want) out[pos] = tid + e * kSelThreads;
+        } else {
+            const int gt_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, (uint32_t)gt_pre));
+            const int eq_before = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, (uint32_t)eq_pre));
+            const int pos = gt_before + min(eq_before, need_eq);
+            if ((is_gt || (is_eq && eq_before < need_eq)) && pos < want) out[pos] = tid + e * kSelThreads;
+        }
     }
 }
 
