@@ -82,7 +82,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int32_t* __restrict__ cu_b, const int32_t* __restrict__ cu_seq, int32_t* __restrict__ indices)
 {
     __shared__ uint32_t narrowed[kCompact * kSelThreads];   // keys still undecided after narrowing (any order)
-    __shared__ int slots[4 * kSelWaves];
     __shared__ int pass_count[3];
     __shared__ int list_n, last_n;                   // fill counts of `narrowed` and `last_keys`
     __shared__ __attribute__((aligned(16))) uint32_t last_keys[64];
@@ -181,14 +180,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         // is exact: the counts are checked, and a bracket that misses the threshold or holds too many keys (heavy
         // ties, adversarial order) falls back to the bit-by-bit passes.
         const int full_regs = n_cand / kSelThreads;              // registers that hold a real key in every thread
-        {
-            // sample i: thread 2 i, a register that runs through [0, full_regs) in scrambled order
-            const int i = tid >> 1;
-            const int my_e = (((i * 97) & (kSamples - 1)) * full_regs) / kSamples;
-            uint32_t sk = 0;
-#pragma unroll
-            for (int e = 0; e < EPT; ++e) sk = e == my_e ? key[e] : sk;
-            if ((tid & 1) == 0) samp[i] = sk;
+        if (tid < kSamples) {
+            // sample i: the token in thread 2 i's register number e_i, where e_i runs through [0, full_regs) in
+            // scrambled order; read once more from memory (it is in the cache) rather than picked out of the registers
+            const int e_i = (((tid * 97) & (kSamples - 1)) * full_regs) / kSamples;
+            samp[tid] = order_key(s[2 * tid + e_i * kSelThreads]);
         }
         __syncthreads();
         if (wave < 2) {
@@ -388,12 +384,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     if (lane < EPT) { chunk_gt[lane * kSelWaves + wave] = my_gt; chunk_eq[lane * kSelWaves + wave] = my_eq; }
     __syncthreads();
     // ... turn the counts into exclusive prefixes over the chunks (one scan for both) ...
-    {
+    if (wave == 0) {
         constexpr int kChunks = EPT * kSelWaves;     // <= 512
-        const int a = tid < kChunks ? chunk_gt[tid] : 0, bq = tid < kChunks ? chunk_eq[tid] : 0;
-        int ea, eb;
-        block_exscan2(a, bq, slots + 2 * kSelWaves, ea, eb);
-        if (tid < kChunks) { chunk_gt[tid] = ea; chunk_eq[tid] = eb; }
+        constexpr int kPer = kChunks / 64;           // consecutive chunks per lane
+        int cg[kPer], ce[kPer], sg = 0, se = 0;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            cg[u] = chunk_gt[lane * kPer + u]; ce[u] = chunk_eq[lane * kPer + u];
+            sg += cg[u]; se += ce[u];
+        }
+        int ig = sg, ie = se;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int tg = __shfl_up(ig, o, 64), te = __shfl_up(ie, o, 64);
+            if (lane >= o) { ig += tg; ie += te; }
+        }
+        int eg = ig - sg, ee = ie - se;              // counts in the lanes before this one
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            chunk_gt[lane * kPer + u] = eg; chunk_eq[lane * kPer + u] = ee;
+            eg += cg[u]; ee += ce[u];
+        }
     }
     __syncthreads();
     // ... and let every kept token compute its output slot: tokens above T before it, plus the kept ties before it.
