@@ -5,6 +5,11 @@
 // definition (sum of weights accumulated in head order, share = (T*S)/sum),
 // so the integers produced are reproducible bit for bit on any IEEE machine.
 // Head-parallel steps (shares, floors, remainder ranks) are order-free.
+//
+// The merge of the score sweeps' per-range row statistics lives here too: it is
+// as small as the allocation, neither depends on the other, and inside one
+// call on one stream a launch costs more than either's work, so the
+// allocation can ride along in extra workgroups of the merge launch.
 #include "common.h"
 
 #pragma clang fp contract(off)
@@ -41,12 +46,13 @@ __device__ __forceinline__ int n_keep_dev(double ratio, int L) {
     return (int)floor(__dadd_rn(__dmul_rn(ratio, (double)L), 0.5));
 }
 
-__global__ __launch_bounds__(kThreads) void allocate_kernel(
+// the whole allocation of pool `seg` by one workgroup of kThreads threads; smem_raw: alloc_smem_bytes(n) bytes
+__device__ __forceinline__ void allocate_pool(
+    unsigned char* smem_raw, const int seg,
     const float* __restrict__ weights, int n_segments, int n, int weight_group, int window,
     const int32_t* __restrict__ cu_seq, double ratio, double beta,
     int32_t* __restrict__ budgets, int32_t* __restrict__ cu_budgets)
 {
-    extern __shared__ unsigned char smem_raw[];
     // layout: S[n] x[n] frac[n] (double) | e[n] (int) | flag[n] (int) | red[kThreads] (ll) | AllocShared
     double* S = reinterpret_cast<double*>(smem_raw);
     double* x = S + n;
@@ -56,7 +62,6 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
     int* e = reinterpret_cast<int*>(sh + 1);
     int* flag = e + n;      // bit 0: capped, bit 1: eligible in the current hand-out round
 
-    const int seg = blockIdx.x;
     const int tid = threadIdx.x;
     const int L = cu_seq[seg + 1] - cu_seq[seg];
     const int nk = n_keep_dev(ratio, L);
@@ -218,15 +223,98 @@ __global__ __launch_bounds__(kThreads) void allocate_kernel(
     }
 }
 
+__global__ __launch_bounds__(kThreads) void allocate_kernel(
+    const float* __restrict__ weights, int n_segments, int n, int weight_group, int window,
+    const int32_t* __restrict__ cu_seq, double ratio, double beta,
+    int32_t* __restrict__ budgets, int32_t* __restrict__ cu_budgets)
+{
+    extern __shared__ unsigned char smem_raw[];
+    allocate_pool(smem_raw, blockIdx.x, weights, n_segments, n, weight_group, window, cu_seq, ratio, beta, budgets, cu_budgets);
+}
+
+// Row r of head `head`: the per-range softmax statistics (reference in base-2 units, sum of exp2) of sweep 1 merged
+// into max + log2(sum). The statistics are fetched sixteen ranges at a time, so that the loads overlap instead of
+// forming a chain of memory latencies as long as the number of ranges, and merged as they come (one pass: a running
+// reference and a sum rescaled when the reference rises). The multiply-adds are written out as fused ones: the
+// result does not depend on how this file is compiled.
+__device__ __forceinline__ void merge_row(const float* __restrict__ stats, int nsplit, int rows_pad, int R,
+                                          int head, int r, float* __restrict__ cst)
+{
+    if (r >= rows_pad) return;
+    float out = INFINITY;
+    if (r < R) {
+        const float2* hs = reinterpret_cast<const float2*>(stats) + (size_t)head * nsplit * rows_pad + r;
+        float M = -INFINITY, Z = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += 16) {
+            float2 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
+            float Mb = M;
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (s0 + u < nsplit && v[u].y > 0.f) Mb = fmaxf(Mb, v[u].x);
+            if (Mb == -INFINITY) continue;                  // nothing seen in these ranges either
+            Z *= __builtin_amdgcn_exp2f(M - Mb);            // exp2(-inf) = 0 while Z is still 0
+            M = Mb;
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (s0 + u < nsplit && v[u].y > 0.f) Z = __builtin_fmaf(v[u].y, __builtin_amdgcn_exp2f(v[u].x - M), Z);
+        }
+        out = M + __log2f(Z);
+    }
+    cst[(size_t)head * rows_pad + r] = out;
+}
+
+// Workgroups [0, alloc_blocks) allocate one pool each (alloc_blocks = 0: none), the others merge kThreads rows each.
+__global__ __launch_bounds__(kThreads) void merge_allocate_kernel(
+    const float* __restrict__ stats, int nsplit, int rows_pad, int R, float* __restrict__ cst, int alloc_blocks,
+    const float* __restrict__ weights, int n_segments, int n, int weight_group, int window,
+    const int32_t* __restrict__ cu_seq, double ratio, double beta,
+    int32_t* __restrict__ budgets, int32_t* __restrict__ cu_budgets)
+{
+    extern __shared__ unsigned char smem_raw[];
+    if ((int)blockIdx.x < alloc_blocks) {          // uniform over the workgroup
+        allocate_pool(smem_raw, blockIdx.x, weights, n_segments, n, weight_group, window, cu_seq, ratio, beta, budgets, cu_budgets);
+        return;
+    }
+    const int mb = blockIdx.x - alloc_blocks;
+    const int blocks_per_head = (rows_pad + kThreads - 1) / kThreads;
+    const int head = mb / blocks_per_head;
+    merge_row(stats, nsplit, rows_pad, R, head, (mb - head * blocks_per_head) * kThreads + threadIdx.x, cst);
+}
+
+size_t alloc_smem_bytes(int n) {
+    return (size_t)n * (3 * sizeof(double) + 2 * sizeof(int)) + kThreads * sizeof(long long) + sizeof(AllocShared) + 16;
+}
+
 }  // namespace
+
+hipError_t launch_score_merge(const Geom& g, const float* stats, int nsplit, int rows_pad, float* cst,
+                              const AllocateJob* job, hipStream_t s)
+{
+    const int n_heads = g.n_items * g.H_kv;
+    const unsigned merge_blocks = (unsigned)(n_heads * ((rows_pad + kThreads - 1) / kThreads));
+    size_t smem = 0;
+    int alloc_blocks = 0;
+    AllocateJob j{};
+    if (job) {
+        j = *job;
+        smem = alloc_smem_bytes(j.heads_per_segment);
+        if (smem > 64 * 1024) return hipErrorInvalidValue;
+        alloc_blocks = j.n_segments;
+    }
+    hipLaunchKernelGGL(merge_allocate_kernel, dim3(merge_blocks + (unsigned)alloc_blocks), dim3(kThreads), smem, s, stats,
+                       nsplit, rows_pad, g.G * g.W, cst, alloc_blocks, j.weights, j.n_segments, j.heads_per_segment,
+                       j.weight_group, g.W, j.cu_seqlens, j.ratio, j.floor_frac, j.budgets, j.cu_budgets);
+    return hipGetLastError();
+}
 
 hipError_t launch_allocate(const Geom& g, const float* weights, int n_segments, int heads_per_segment,
                            int weight_group, const int32_t* cu_seqlens, double ratio, double floor_frac,
                            int32_t* budgets, int32_t* cu_budgets, hipStream_t s)
 {
     const int n = heads_per_segment;
-    const size_t smem = (size_t)n * (3 * sizeof(double) + 2 * sizeof(int)) + kThreads * sizeof(long long) +
-                        sizeof(AllocShared) + 16;
+    const size_t smem = alloc_smem_bytes(n);
     if (smem > 64 * 1024) return hipErrorInvalidValue;   // caller limits heads_per_segment
     hipLaunchKernelGGL(allocate_kernel, dim3(n_segments), dim3(kThreads), smem, s, weights, n_segments, n,
                        weight_group, g.W, cu_seqlens, ratio, floor_frac, budgets, cu_budgets);

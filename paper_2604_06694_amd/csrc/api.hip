@@ -494,11 +494,17 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     if (side) helper_lock.lock();
 #define AUDIOKV_MARK(i) do { if (prof) AUDIOKV_HIP(hipEventRecord(g_prof.ev[i], s), "hipEventRecord"); } while (0)
     AUDIOKV_MARK(0);
-    if (!side) {
+    // In line and without stage timing, the allocation rides along with the launch that merges the row statistics
+    // between the two sweeps (one launch less on the critical path of a call); with the caller's log-sum-exp there
+    // is no such launch.
+    const AllocateJob alloc_job{weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
+                                budgets_dev, cu_budgets_dev};
+    const bool ride = !side && !prof && !lse_dev;
+    if (!side && !ride) {
         // (stage timing wants one kernel per interval: then, too, the allocation stays in line)
         AUDIOKV_HIP(launch_allocate(g, weights_dev, n_seg, hps, 1, cu_seqlens_dev, ratio, (double)params->floor_frac,
                                     budgets_dev, cu_budgets_dev, s), "allocate kernel");
-    } else {
+    } else if (side) {
         AUDIOKV_HIP(ensure_helper(), "helper stream");
         AUDIOKV_HIP(hipEventRecord(g_helper.fork, s), "hipEventRecord");
         AUDIOKV_HIP(hipStreamWaitEvent(g_helper.stream, g_helper.fork, 0), "hipStreamWaitEvent");
@@ -515,7 +521,7 @@ int32_t evict_entry(const audiokv_params* params, const void* q_win, const void*
     AUDIOKV_HIP(launch_score(g, q_win, k, cu_seqlens_dev, seqlens_host, stats, raw, s,
                              prof ? g_prof.ev[AUDIOKV_PROFILE_STAGES + 1] : nullptr, lse_dev,
                              w.raw2 ? reinterpret_cast<float*>(ws + w.raw2_off) : nullptr,
-                             (size_t)b.total_tokens * params->n_kv_heads), "score kernels");
+                             (size_t)b.total_tokens * params->n_kv_heads, ride ? &alloc_job : nullptr), "score kernels");
     AUDIOKV_MARK(2);
     if (side) {
         // budgets (needed by select) and filters (needed by smooth) are ready; by now the helper's work is long done

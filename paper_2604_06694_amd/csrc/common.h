@@ -45,6 +45,17 @@ __device__ __forceinline__ int64_t kv_row_offset(const Geom& g, int item, int64_
 
 // ---- launchers (defined in the .hip files, called from api.hip) ------------
 
+// Arguments of launch_allocate, for callers that let the allocation ride along with another small launch.
+struct AllocateJob {
+    const float* weights; int n_segments, heads_per_segment, weight_group; const int32_t* cu_seqlens;
+    double ratio, floor_frac; int32_t* budgets; int32_t* cu_budgets;
+};
+// Merge of the per-range row statistics of sweep 1 (stats: [head][nsplit][rows_pad][2]) into one constant per row
+// (cst: [head][rows_pad], max + log2(sum); +inf for rows >= R). With `job`, the same launch also runs the budget
+// allocation in extra workgroups: neither depends on the other, and each launch costs more than either's work.
+hipError_t launch_score_merge(const Geom& g, const float* stats, int nsplit, int rows_pad, float* cst,
+                              const AllocateJob* job, hipStream_t s);
+
 // Number of key-range splits per head used by the score kernels; a pure
 // function of the batch so that the workspace query and the launch agree.
 int score_num_splits(int H_kv, int n_items, const int32_t* seqlens_host, int rows, int D);
@@ -53,10 +64,12 @@ int score_padded_rows(int rows, int D);
 
 // between_sweeps: optional event recorded on `s` after the first sweep (timing aid), or nullptr.
 // lse: optional fp32 [items][H_q][W] natural-log softmax denominators of the window rows; given, sweep 1 is skipped.
+// ride_along: optional allocation to run in the launch that merges the row statistics (ignored with lse: the caller
+// must check score_merge_runs(lse) and launch the allocation itself when there is no merge).
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         const int32_t* seqlens_host, float* stats_ws, float* raw_out, hipStream_t s,
                         hipEvent_t between_sweeps = nullptr, const float* lse = nullptr,
-                        float* raw_second = nullptr, size_t raw_elems = 0);
+                        float* raw_second = nullptr, size_t raw_elems = 0, const AllocateJob* ride_along = nullptr);
 // More than 448 window rows (d <= 128): sweep 2 runs as two launches and needs a second buffer of the size of the
 // scores (raw_second, raw_elems floats).
 bool score_needs_second_raw(int rows, int D);

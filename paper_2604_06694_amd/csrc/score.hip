@@ -115,7 +115,7 @@ int score_num_splits(int H_kv, int n_items, const int32_t* seqlens_host, int row
 
 hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const int32_t* cu_seqlens,
                         const int32_t* seqlens_host, float* stats_ws, float* raw_out, hipStream_t s, hipEvent_t between_sweeps,
-                        const float* lse, float* raw_second, size_t raw_elems)
+                        const float* lse, float* raw_second, size_t raw_elems, const AllocateJob* ride_along)
 {
     Plan p1;
     const int rows = g.G * g.W;
@@ -135,6 +135,10 @@ hipError_t launch_score(const Geom& g, const void* q_win, const void* k, const i
     };
     hipError_t e = sweep(1, p1, ns1, 0, raw_out);
     if (e != hipSuccess) return e;
+    if (!lse) {
+        e = launch_score_merge(g, stats_ws, ns1, rows_pad, cst, ride_along, s);
+        if (e != hipSuccess) return e;
+    }
     if (between_sweeps) {
         e = hipEventRecord(between_sweeps, s);
         if (e != hipSuccess) return e;

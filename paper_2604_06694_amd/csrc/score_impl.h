@@ -588,40 +588,6 @@ __global__ __launch_bounds__(64 * (WR + 1), (NB == 1 && D <= 128) ? 4 : 2) void 
 }
 
 // per row: reference + log2(sum) over the key ranges (fixed order); +inf for padded rows, whose exp2 then vanishes.
-// One thread per row, 64 rows per workgroup. The per-range statistics are fetched sixteen at a time, so that the
-// loads overlap instead of forming a chain of memory latencies as long as the number of ranges, and merged as they
-// come (one pass: a running reference and a sum rescaled when the reference rises).
-static __global__ __launch_bounds__(64) void score_merge_kernel(const float* __restrict__ stats, int nsplit,
-                                                                int rows_pad, int R, float* __restrict__ cst)
-{
-    const int blocks_per_head = (rows_pad + 63) / 64;
-    const int head = blockIdx.x / blocks_per_head;
-    const int r = (blockIdx.x - head * blocks_per_head) * 64 + threadIdx.x;
-    if (r >= rows_pad) return;
-    float out = INFINITY;
-    if (r < R) {
-        const float2* hs = reinterpret_cast<const float2*>(stats) + (size_t)head * nsplit * rows_pad + r;
-        float M = -INFINITY, Z = 0.f;
-        for (int s0 = 0; s0 < nsplit; s0 += 16) {
-            float2 v[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) v[u] = hs[(size_t)min(s0 + u, nsplit - 1) * rows_pad];
-            float Mb = M;
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (s0 + u < nsplit && v[u].y > 0.f) Mb = fmaxf(Mb, v[u].x);
-            if (Mb == -INFINITY) continue;                  // nothing seen in these ranges either
-            Z *= fast_exp2(M - Mb);                         // exp2(-inf) = 0 while Z is still 0
-            M = Mb;
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (s0 + u < nsplit && v[u].y > 0.f) Z += v[u].y * fast_exp2(v[u].x - M);
-        }
-        out = M + __log2f(Z);
-    }
-    cst[(size_t)head * rows_pad + r] = out;
-}
-
 // Row constants from log-sum-exp values that the caller already has (natural log of the softmax denominator of
 // every window row, as an attention kernel that ran the window's queries returns them): replaces sweep 1.
 static __global__ __launch_bounds__(64) void score_cst_from_lse_kernel(Geom g, const float* __restrict__ lse,
@@ -646,8 +612,8 @@ static __global__ __launch_bounds__(256) void score_add_kernel(float* __restrict
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) raw[i] += raw_b[i];
 }
 
-// which = 1: row statistics (sweep 1 and the merge, or the conversion of supplied log-sum-exp values) into
-//            cst = stats + n_heads * nsplit * rows_pad * 2;
+// which = 1: per-range row statistics into stats (sweep 1; the caller merges them into cst with launch_score_merge),
+//            or the conversion of supplied log-sum-exp values straight into cst;
 // which = 2: column sums (sweep 2) from the cst at cst_in. The two may use different (NB, WR) tilings and key-range
 // counts: they only share the row pitch rows_pad of the statistics.
 template <int D, int NB, int WR>
@@ -676,8 +642,6 @@ hipError_t launch_sweep(int which, const Geom& g, const void* q_win, const void*
             hipLaunchKernelGGL((score_kernel<D, NB, WR, false>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
                                (const __bf16*)q_win, (const __bf16*)k, cu_seq, nsplit, rows_pad, 0, stats,
                                (const float*)nullptr, raw);
-            hipLaunchKernelGGL(score_merge_kernel, dim3(merge_blocks), dim3(64), 0, s, (const float*)stats, nsplit,
-                               rows_pad, g.G * g.W, cst);
         }
     } else {
         hipLaunchKernelGGL((score_kernel<D, NB, WR, true>), grid, dim3(T::THREADS), T::LDS_BYTES, s, g,
