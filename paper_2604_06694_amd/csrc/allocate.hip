@@ -29,15 +29,16 @@ struct AllocShared {
     int granted;
 };
 
-// Sum of an int array over the block (order does not matter for integers).
-__device__ long long block_sum_ll(long long v, long long* scratch /* [kThreads] */) {
-    scratch[threadIdx.x] = v;
+// Sum of one integer per thread over the block (order does not matter for integers): lanes by shuffles, the four
+// waves through `scratch` (at least kThreads / 64 entries). Two barriers: the second frees `scratch` for the next use.
+__device__ long long block_sum_ll(long long v, long long* scratch) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (int s = kThreads / 2; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) scratch[threadIdx.x] += scratch[threadIdx.x + s];
-        __syncthreads();
-    }
-    const long long r = scratch[0];
+    long long r = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) r += scratch[w];
     __syncthreads();
     return r;
 }
@@ -199,22 +200,24 @@ __device__ __forceinline__ void allocate_pool(
     const int h0 = min(tid * per, n), h1 = min(h0 + per, n);
     long long chunk = 0;
     for (int h = h0; h < h1; ++h) chunk += f + e[h];
-    red[tid] = chunk;
-    __syncthreads();
-    // exclusive scan of the 256 chunk totals (integers: any order), total to the last segment's end marker
-    const long long mine = chunk;
-    for (int off = 1; off < kThreads; off <<= 1) {
-        const long long add = tid >= off ? red[tid - off] : 0;
-        __syncthreads();
-        red[tid] += add;
-        __syncthreads();
+    // exclusive scan of the 256 chunk totals (integers: any order): lanes by shuffles, waves through `red`;
+    // the total goes to the last segment's end marker
+    long long incl = chunk;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long t = __shfl_up(incl, off, 64);
+        if ((tid & 63) >= off) incl += t;
     }
-    if (tid == kThreads - 1 && seg == n_segments - 1) cu_budgets[(size_t)n_segments * n] = (int32_t)(base + red[tid]);
-    const long long excl = red[tid] - mine;
+    if ((tid & 63) == 63) red[tid >> 6] = incl;
     __syncthreads();
-    red[tid] = excl;
-    __syncthreads();
-    long long run = base + red[tid];
+    long long before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < (tid >> 6)) before += red[w];
+        total += red[w];
+    }
+    if (tid == 0 && seg == n_segments - 1) cu_budgets[(size_t)n_segments * n] = (int32_t)(base + total);
+    long long run = base + before + incl - chunk;
     for (int h = h0; h < h1; ++h) {
         const int b = f + e[h];
         budgets[(size_t)seg * n + h] = b;
