@@ -255,7 +255,10 @@ int32_t audiokv_compact(const audiokv_params* params,
  * the tables that smoothing needs for lengths that are not powers of two: for
  * pools of 32 heads or more, or when such tables are needed, they are forked
  * onto a helper stream owned by the library (created on first use, default
- * priority) and joined back into `stream` with events after the scoring; everything is ordered after prior work on
+ * priority) and joined back into `stream` with events after the scoring
+ * (smaller pools are allocated on `stream` itself, in the launch that merges
+ * the softmax statistics between the two scoring sweeps); everything is
+ * ordered after prior work on
  * `stream` and before later work on it. Calls on different streams may be in
  * flight together (separate workspaces and outputs), also from several host
  * threads: the helper stream and its two events are shared, so the part of a
