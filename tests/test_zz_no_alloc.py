@@ -61,3 +61,51 @@ def test_noalloc_rejects_what_does_not_fit():
     rc = B._lib.audiokv_evict_noalloc(C.byref(cp), one, one, one, one, 0, one, arr, len(lens), 0.4, 0.125, 1.0,
                                       one, one, one, one, one, None)
     assert rc == -3 and b"scratch" in B._lib.audiokv_last_error()
+
+
+def test_noalloc_call_replays_from_a_captured_graph():
+    """The entry point exists for callers that cannot allocate, such as code under graph capture: a captured call must
+    give the eager result on every replay, with eager calls (other sizes, same static scratch) between the replays."""
+    import paper_2604_06694_amd as A
+    rng = np.random.default_rng(77)
+    dev = torch.device("cuda:0")
+    H_q, H_kv, d, W, L = 28, 4, 128, 32, 4096
+    q = bf16_tensor(f64_to_bf16_bits(rng.standard_normal((H_q, W, d))).reshape(-1))
+    k = bf16_tensor(f64_to_bf16_bits(rng.standard_normal((H_kv, L, d)) * 2.0).reshape(-1))
+    v = bf16_tensor(f64_to_bf16_bits(rng.standard_normal((H_kv, L, d))).reshape(-1))
+    w = torch.from_numpy(rng.gamma(1.0, size=H_kv).astype(np.float32)).to(dev)
+    p = A.Params(H_q, H_kv, d, W)
+    ref = A.evict(p, q, k, v, w, [L], 0.4, 0.125, 1.0, alloc_scope=A.SCOPE_ITEM)
+    torch.cuda.synchronize()
+    rows = ref["total_rows"]
+    out = {"k_out": torch.zeros((rows, d), dtype=torch.bfloat16, device=dev),
+           "v_out": torch.zeros((rows, d), dtype=torch.bfloat16, device=dev),
+           "indices": torch.full((rows,), -1, dtype=torch.int32, device=dev),
+           "budgets": torch.zeros(H_kv, dtype=torch.int32, device=dev),
+           "cu_budgets": torch.zeros(H_kv + 1, dtype=torch.int32, device=dev)}
+    cu = torch.tensor([0, L], dtype=torch.int32, device=dev)
+
+    def call():
+        A.evict_noalloc(p, q, k, v, w, [L], 0.4, 0.125, 1.0, out, alloc_scope=A.SCOPE_ITEM, cu_seqlens=cu)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                      # first call outside the capture: attributes, the scratch address
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        _case(A, rng, 8, 2, 128, 16, [1000 + 300 * rep], 0.5, 0.25)      # eager work that overwrites the scratch
+        out["indices"].fill_(-1)
+        out["k_out"].zero_()
+        out["v_out"].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out["budgets"], ref["budgets"]) and torch.equal(out["cu_budgets"], ref["cu_budgets"]), rep
+        assert torch.equal(out["indices"], ref["indices"][:rows]), rep
+        assert torch.equal(out["k_out"].view(torch.int16), ref["k_out"][:rows].view(torch.int16)), rep
+        assert torch.equal(out["v_out"].view(torch.int16), ref["v_out"][:rows].view(torch.int16)), rep
