@@ -181,10 +181,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         // ties, adversarial order) falls back to the bit-by-bit passes.
         const int full_regs = n_cand / kSelThreads;              // registers that hold a real key in every thread
         if (tid < kSamples) {
-            // sample i: the token in thread 2 i's register number e_i, where e_i runs through [0, full_regs) in
-            // scrambled order; read once more from memory (it is in the cache) rather than picked out of the registers
-            const int e_i = (((tid * 97) & (kSamples - 1)) * full_regs) / kSamples;
-            samp[tid] = order_key(s[2 * tid + e_i * kSelThreads]);
+            // sample i: token 2 i or 2 i + 1 (both parities occur) of the block of 1024 tokens number e_i, where e_i
+            // runs through [0, full_regs) in scrambled order; read once more from memory (it is in the cache) rather
+            // than picked out of the registers
+            const int hashed = (tid * 97) & (kSamples - 1);
+            const int e_i = (hashed * full_regs) / kSamples;
+            samp[tid] = order_key(s[2 * tid + ((hashed >> 4) & 1) + e_i * kSelThreads]);
         }
         __syncthreads();
         if (wave < 2) {
