@@ -68,7 +68,9 @@ def algorithmic_bytes(cfg, lens, ratio):
 def measured_traffic(workload: str) -> dict:
     """HBM bytes per launch measured with rocprofv3 --pmc for this workload's default settings, as recorded
     (already scaled by the copy-kernel calibration) in profiles/<workload>_hbm_traffic.md; {} if absent."""
-    short = {"cfg3_long_audio_L32768": "evict_cfg3_L32768_hbm_traffic.md"}.get(workload)
+    short = {"cfg3_long_audio_L32768": "evict_cfg3_L32768_hbm_traffic.md",
+             "cfg2_qwen25_omni_7b_L8192": "evict_cfg2_L8192_hbm_traffic.md",
+             "cfg4_qwen3_omni_30b_L16384": "evict_cfg4_L16384_hbm_traffic.md"}.get(workload)
     path = os.path.join(ROOT, "profiles", short) if short else None
     out = {}
     if path and os.path.exists(path):
